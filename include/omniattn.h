@@ -1,0 +1,157 @@
+/*
+ * omniattn.h - C ABI of the MI355X (gfx950) sparse MLA decode library.
+ *
+ * One operation: decode-phase attention for absorbed multi-head latent
+ * attention, restricted to the KV positions that OmniAttn's cache-compression
+ * rule keeps.  For sequence b of length L_b the kept set is the first S
+ * ("sink") positions and the last W ("recent") positions, as a set union
+ * clipped to [0, L_b) (paper section 3.2.1, second equation, 0-based here),
+ * and the result is softmax(q K_M^T * scale) V_M over that set (left-hand side
+ * of the first equation of 3.2.1).  One (S, W) applies to every head of the
+ * call (section 3.2.2: the layer, not the head, is the unit of compression).
+ *
+ * MLA layout (the paper only names MLA as compatible; shapes are the
+ * DeepSeek-R1 absorbed decode form): each cached token is one latent row of
+ * 576 numbers; the key is the whole row, the value is its first 512 numbers;
+ * queries arrive already multiplied by the key up-projection.
+ *
+ * Conventions
+ *   - All data pointers marked "device" are HIP device pointers owned by the
+ *     caller; "host" pointers are ordinary memory.  The library owns only the
+ *     plan object and the small device metadata it uploads for it.
+ *   - `hip_stream` is a hipStream_t cast to void* (NULL = the null stream).
+ *   - Every function returns 0 on success or a negative OMNIATTN_E* code.
+ *     Nothing aborts and no C++ exception crosses this boundary.
+ *   - The library is a HIP library: there is no CPU fallback.  On a machine
+ *     without a usable GPU, omniattn_plan() and omniattn_decode() fail with
+ *     OMNIATTN_EHIP; only the host-side planner (omniattn_plan_host) works.
+ */
+#ifndef OMNIATTN_H
+#define OMNIATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OMNIATTN_QK_DIM 576
+#define OMNIATTN_V_DIM 512
+#define OMNIATTN_PAGE 128
+
+enum { OMNIATTN_BF16 = 0, OMNIATTN_FP8_E4M3 = 1, OMNIATTN_FP32 = 2 };
+
+enum {
+  OMNIATTN_OK = 0,
+  OMNIATTN_EINVAL = -1,       /* null pointer, bad shape, bad size            */
+  OMNIATTN_EUNSUPPORTED = -2, /* dtype / head count / dims not supported      */
+  OMNIATTN_EWORKSPACE = -3,   /* workspace missing or too small               */
+  OMNIATTN_EHIP = -4,         /* a HIP call failed; see omniattn_last_hip_error */
+  OMNIATTN_ENOMEM = -5        /* host allocation failed                       */
+};
+
+/* Statement of one decode problem.  Fixed by the plan; the tensors come later. */
+typedef struct {
+  int32_t batch;             /* B >= 1 sequences                                        */
+  int32_t num_heads;         /* H >= 1 query heads sharing each sequence's latent cache */
+  int32_t qk_dim;            /* must be 576                                             */
+  int32_t v_dim;             /* must be 512 (value = first 512 numbers of a cache row)  */
+  int32_t page_size;         /* must be 128 tokens                                      */
+  int32_t max_pages_per_seq; /* row stride of page_table, in int32 elements             */
+  int64_t num_pages;         /* pages in the pool (for validation of host inputs only)  */
+  int32_t sink;              /* S = N_sink  >= 0                                        */
+  int32_t window;            /* W = N_recent >= 0; S + W >= L_b means dense attention   */
+  float softmax_scale;       /* multiplies q.k before the softmax                       */
+  int32_t kv_dtype;          /* OMNIATTN_BF16 | OMNIATTN_FP8_E4M3 (OCP e4m3, finite-only;
+                                one fp32 scale per token multiplies the whole row)      */
+  int32_t out_dtype;         /* OMNIATTN_BF16 | OMNIATTN_FP32                           */
+  int32_t num_splits_hint;   /* 0: the library balances work over the GPU's compute
+                                units.  n > 0: every sequence's retained tiles are cut
+                                into min(n, tiles) pieces (for tests of the split path) */
+} omniattn_problem_t;
+
+typedef struct omniattn_plan_s omniattn_plan_t; /* opaque, library-owned */
+
+/*
+ * Steps a1/a2 of the path: build the retained ranges of every sequence (second
+ * equation of 3.2.1), cut them into KV tiles, partition tiles into work units
+ * and size the workspace.  `seq_lens_host` is a host array of B context
+ * lengths L_b >= 0 (the token being decoded is already in the cache and is
+ * counted).  Requires ceil(L_b/128) <= max_pages_per_seq.
+ *
+ * omniattn_plan      also uploads the metadata to the current HIP device
+ *                    (synchronously; uses hipMalloc) so that omniattn_decode
+ *                    can run.  Work is balanced over that device's CU count.
+ * omniattn_plan_host builds the same plan for `num_cus` compute units without
+ *                    touching HIP; such a plan can be inspected but
+ *                    omniattn_decode on it returns OMNIATTN_EINVAL.
+ * On failure *plan_out is set to NULL.
+ */
+int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
+                  const int32_t* seq_lens_host);
+int omniattn_plan_host(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
+                       const int32_t* seq_lens_host, int32_t num_cus);
+void omniattn_plan_destroy(omniattn_plan_t* plan); /* NULL is allowed */
+
+/* Introspection (host only, cheap). */
+size_t omniattn_plan_workspace_bytes(const omniattn_plan_t* plan); /* may be 0 */
+int64_t omniattn_plan_retained_tokens(const omniattn_plan_t* plan); /* sum_b |M_b| */
+int32_t omniattn_plan_num_units(const omniattn_plan_t* plan);      /* grid of the main kernel */
+int32_t omniattn_plan_num_segments(const omniattn_plan_t* plan);
+int32_t omniattn_plan_num_partials(const omniattn_plan_t* plan);   /* partial results the combine kernel merges */
+int32_t omniattn_plan_max_splits(const omniattn_plan_t* plan);     /* most pieces any one sequence was cut into */
+int32_t omniattn_plan_tile_tokens(const omniattn_plan_t* plan);    /* KV tokens per tile */
+int32_t omniattn_plan_head_block(const omniattn_plan_t* plan);     /* heads per work unit */
+
+/*
+ * Copy out the plan's segments, 8 int32 each:
+ *   [0] sequence b          [1] head block index     [2] first tile  [3] end tile
+ *   [4] partial slot or -1  [5] work unit            [6] L_b         [7] tiles of b
+ * Tiles are numbered along the sequence's retained tiles in ascending position.
+ * Returns the number of segments written (<= cap) or a negative error.
+ */
+int32_t omniattn_plan_get_segments(const omniattn_plan_t* plan, int32_t* buf, int32_t cap);
+/*
+ * Logical token range [*lo, *hi) that retained tile `tile` of sequence `b`
+ * spans (tile-aligned; the retained predicate still applies inside it).
+ */
+int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t tile,
+                             int32_t* lo, int32_t* hi);
+
+/*
+ * Steps a3-a9: gather retained tiles through the page table, QK^T, masking of
+ * partial tiles, online softmax, PV, normalisation, and (when some sequence was
+ * split) the combine pass.  Asynchronous on `hip_stream`; allocates nothing and
+ * does not synchronise.
+ *
+ *   q          device, bf16 [B, H, 576] contiguous (absorbed queries)
+ *   kv_cache   device, bf16 or e4m3 bytes [num_pages, 128, 576] contiguous
+ *   kv_scales  device, fp32 [num_pages, 128]; NULL unless kv_dtype is fp8
+ *   page_table device, int32 [B, max_pages_per_seq]; entry i of row b is the
+ *              physical page of logical tokens [128 i, 128 i + 128).  Entries of
+ *              pages that hold no retained token are never read.
+ *   out        device, out_dtype [B, H, 512]
+ *   lse        device, fp32 [B, H]: natural-log sum of exp(scale * q.k_j) over
+ *              the retained j.  An empty retained set gives out = 0, lse = -inf.
+ *   workspace  device, at least omniattn_plan_workspace_bytes(plan) bytes,
+ *              256-byte aligned; may be NULL when that is 0.  Two decodes in
+ *              flight at once need two workspaces.
+ *
+ * Slots outside the retained set, and pages not referenced, may hold anything
+ * (NaN included) without effect.  Page ids of retained pages must lie in
+ * [0, num_pages): the kernel does not check device-side contents.
+ * Same plan + same inputs give bitwise identical results (no atomics).
+ */
+int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
+                    const float* kv_scales, const int32_t* page_table, void* out,
+                    float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+const char* omniattn_strerror(int code);
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char* omniattn_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMNIATTN_H */

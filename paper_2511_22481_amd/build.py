@@ -1,0 +1,47 @@
+"""Compile the HIP library for gfx950 in-tree (paper_2511_22481_amd/libomniattn.so)."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libomniattn.so")
+SOURCES = ["decode_kernels.hip", "api.cpp", "plan.cpp"]
+HEADERS = ["kernels.h", "plan.h", os.path.join("..", "..", "include", "omniattn.h")]
+
+
+def hipcc():
+    for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if c and (os.path.isabs(c) and os.path.exists(c) or not os.path.isabs(c)):
+            return c
+    return "hipcc"
+
+
+def is_stale():
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
+
+
+def build(force=True, verbose=False):
+    """hipcc --offload-arch=gfx950, one shared library.  Packed-fp32 code generation
+    is switched off for the device pass."""
+    if not force and not is_stale():
+        return LIB
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument", "-x", "hip"]
+    cmd += [os.path.join(CSRC, f) for f in SOURCES]
+    cmd += ["-o", LIB]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(res.stdout)
+        print("\n".join(l for l in res.stderr.splitlines()
+                        if "packed-fp32-ops" not in l))
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed")
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,229 @@
+// C ABI of the sparse MLA decode library (see include/omniattn.h).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+
+#include "kernels.h"
+#include "plan.h"
+
+using namespace omniattn;
+
+struct omniattn_plan_s {
+  HostPlan hp;
+  bool on_device = false;
+  int device = -1;
+  // device copies of the plan metadata (owned)
+  int32_t* d_unit_seg = nullptr;
+  Segment* d_segs = nullptr;
+  CombineItem* d_combine = nullptr;
+};
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e, const char* what) {
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  (void)hipGetLastError();  // clear the sticky "last error" so later calls are not blamed
+  return OMNIATTN_EHIP;
+}
+
+#define OA_HIP(call)                                  \
+  do {                                                \
+    hipError_t e_ = (call);                           \
+    if (e_ != hipSuccess) return hip_fail(e_, #call); \
+  } while (0)
+
+std::once_flag g_init_once;
+hipError_t g_init_status = hipSuccess;
+
+void free_device(omniattn_plan_s* pl) {
+  if (pl->d_unit_seg) (void)hipFree(pl->d_unit_seg);
+  if (pl->d_segs) (void)hipFree(pl->d_segs);
+  if (pl->d_combine) (void)hipFree(pl->d_combine);
+  pl->d_unit_seg = nullptr;
+  pl->d_segs = nullptr;
+  pl->d_combine = nullptr;
+}
+
+int make_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob, const int32_t* seq_lens,
+              int num_cus) {
+  omniattn_plan_s* pl = new (std::nothrow) omniattn_plan_s();
+  if (!pl) return OMNIATTN_ENOMEM;
+  int rc;
+  try {
+    rc = build_host_plan(pl->hp, *prob, seq_lens, num_cus);
+  } catch (const std::bad_alloc&) {
+    rc = OMNIATTN_ENOMEM;
+  } catch (...) {
+    rc = OMNIATTN_EINVAL;
+  }
+  if (rc != OMNIATTN_OK) {
+    delete pl;
+    return rc;
+  }
+  *plan_out = pl;
+  return OMNIATTN_OK;
+}
+
+template <class T>
+int upload(T** dst, const std::vector<T>& src) {
+  *dst = nullptr;
+  if (src.empty()) return OMNIATTN_OK;
+  OA_HIP(hipMalloc((void**)dst, src.size() * sizeof(T)));
+  OA_HIP(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+  return OMNIATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int omniattn_plan_host(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
+                       const int32_t* seq_lens_host, int32_t num_cus) {
+  if (!plan_out) return OMNIATTN_EINVAL;
+  *plan_out = nullptr;
+  if (!prob || !seq_lens_host) return OMNIATTN_EINVAL;
+  return make_plan(plan_out, prob, seq_lens_host, num_cus);
+}
+
+int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
+                  const int32_t* seq_lens_host) {
+  if (!plan_out) return OMNIATTN_EINVAL;
+  *plan_out = nullptr;
+  if (!prob || !seq_lens_host) return OMNIATTN_EINVAL;
+  int dev = 0;
+  OA_HIP(hipGetDevice(&dev));
+  int cus = 0;
+  OA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  std::call_once(g_init_once, [] { g_init_status = init_kernels(); });
+  if (g_init_status != hipSuccess) return hip_fail(g_init_status, "kernel attribute setup");
+
+  omniattn_plan_s* pl = nullptr;
+  int rc = make_plan(&pl, prob, seq_lens_host, cus > 0 ? cus : 256);
+  if (rc != OMNIATTN_OK) return rc;
+  pl->device = dev;
+  rc = upload(&pl->d_unit_seg, pl->hp.unit_seg);
+  if (rc == OMNIATTN_OK) rc = upload(&pl->d_segs, pl->hp.segs);
+  if (rc == OMNIATTN_OK) rc = upload(&pl->d_combine, pl->hp.combine);
+  if (rc != OMNIATTN_OK) {
+    free_device(pl);
+    delete pl;
+    return rc;
+  }
+  pl->on_device = true;
+  *plan_out = pl;
+  return OMNIATTN_OK;
+}
+
+void omniattn_plan_destroy(omniattn_plan_t* plan) {
+  if (!plan) return;
+  free_device(plan);
+  delete plan;
+}
+
+size_t omniattn_plan_workspace_bytes(const omniattn_plan_t* plan) {
+  return plan ? plan->hp.workspace_bytes : 0;
+}
+int64_t omniattn_plan_retained_tokens(const omniattn_plan_t* plan) {
+  return plan ? plan->hp.retained_tokens : 0;
+}
+int32_t omniattn_plan_num_units(const omniattn_plan_t* plan) {
+  return plan ? (int32_t)plan->hp.unit_seg.size() - 1 : 0;
+}
+int32_t omniattn_plan_num_segments(const omniattn_plan_t* plan) {
+  return plan ? (int32_t)plan->hp.segs.size() : 0;
+}
+int32_t omniattn_plan_num_partials(const omniattn_plan_t* plan) { return plan ? plan->hp.n_slots : 0; }
+int32_t omniattn_plan_max_splits(const omniattn_plan_t* plan) { return plan ? plan->hp.max_splits : 0; }
+int32_t omniattn_plan_tile_tokens(const omniattn_plan_t*) { return kTile; }
+int32_t omniattn_plan_head_block(const omniattn_plan_t* plan) { return plan ? plan->hp.head_block : 0; }
+
+int32_t omniattn_plan_get_segments(const omniattn_plan_t* plan, int32_t* buf, int32_t cap) {
+  if (!plan || (!buf && cap > 0) || cap < 0) return OMNIATTN_EINVAL;
+  int32_t n = (int32_t)plan->hp.segs.size();
+  if (n > cap) n = cap;
+  static_assert(sizeof(Segment) == 8 * sizeof(int32_t), "segment layout is part of the ABI");
+  if (n > 0) std::memcpy(buf, plan->hp.segs.data(), (size_t)n * sizeof(Segment));
+  return n;
+}
+
+int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t tile, int32_t* lo,
+                             int32_t* hi) {
+  if (!plan || !lo || !hi || b < 0 || b >= plan->hp.prob.batch) return OMNIATTN_EINVAL;
+  TileLayout tl = tile_layout(plan->hp.seq_lens[b], plan->hp.prob.sink, plan->hp.prob.window);
+  if (tile < 0 || tile >= tl.count()) return OMNIATTN_EINVAL;
+  *lo = tl.logical(tile) * kTile;
+  *hi = *lo + kTile;
+  return OMNIATTN_OK;
+}
+
+int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
+                    const float* kv_scales, const int32_t* page_table, void* out, float* lse,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!plan || !q || !kv_cache || !page_table || !out || !lse) return OMNIATTN_EINVAL;
+  if (!plan->on_device) return OMNIATTN_EINVAL;
+  const HostPlan& hp = plan->hp;
+  const bool fp8 = hp.prob.kv_dtype == OMNIATTN_FP8_E4M3;
+  if (fp8 && !kv_scales) return OMNIATTN_EINVAL;
+  if (hp.workspace_bytes > 0) {
+    if (!workspace || workspace_bytes < hp.workspace_bytes) return OMNIATTN_EWORKSPACE;
+    if (((uintptr_t)workspace & 255) != 0) return OMNIATTN_EWORKSPACE;
+  }
+  if ((((uintptr_t)q | (uintptr_t)kv_cache | (uintptr_t)out) & 15) != 0) return OMNIATTN_EINVAL;
+  hipStream_t stream = (hipStream_t)hip_stream;
+
+  DecodeParams dp;
+  dp.q = (const uint16_t*)q;
+  dp.kv = (const uint8_t*)kv_cache;
+  dp.kv_scales = kv_scales;
+  dp.page_table = page_table;
+  dp.out = out;
+  dp.lse = lse;
+  dp.part_o = (float*)workspace;
+  dp.part_lse = dp.part_o ? dp.part_o + (size_t)hp.n_slots * hp.head_block * kV : nullptr;
+  dp.unit_seg = plan->d_unit_seg;
+  dp.segs = plan->d_segs;
+  dp.H = hp.prob.num_heads;
+  dp.max_pages = hp.prob.max_pages_per_seq;
+  dp.S = hp.prob.sink;
+  dp.W = hp.prob.window;
+  dp.head_block = hp.head_block;
+  dp.out_fp32 = hp.prob.out_dtype == OMNIATTN_FP32;
+  dp.scale_log2 = hp.prob.softmax_scale * 1.4426950408889634f;
+  OA_HIP(launch_decode(dp, hp.waves, fp8, (int)hp.unit_seg.size() - 1, stream));
+
+  if (!hp.combine.empty()) {
+    CombineParams cp;
+    cp.items = plan->d_combine;
+    cp.part_o = dp.part_o;
+    cp.part_lse = dp.part_lse;
+    cp.out = out;
+    cp.lse = lse;
+    cp.H = dp.H;
+    cp.head_block = hp.head_block;
+    cp.out_fp32 = dp.out_fp32;
+    OA_HIP(launch_combine(cp, (int)hp.combine.size(), stream));
+  }
+  return OMNIATTN_OK;
+}
+
+const char* omniattn_strerror(int code) {
+  switch (code) {
+    case OMNIATTN_OK: return "ok";
+    case OMNIATTN_EINVAL: return "invalid argument";
+    case OMNIATTN_EUNSUPPORTED: return "unsupported dtype, head count or dimension";
+    case OMNIATTN_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case OMNIATTN_EHIP: return "HIP call failed (see omniattn_last_hip_error)";
+    case OMNIATTN_ENOMEM: return "out of host memory";
+    default: return "unknown error code";
+  }
+}
+
+const char* omniattn_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

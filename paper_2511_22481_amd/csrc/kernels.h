@@ -1,0 +1,40 @@
+// Launch interface between the C ABI (api.cpp) and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.h"
+
+namespace omniattn {
+
+struct DecodeParams {
+  const uint16_t* q;
+  const uint8_t* kv;
+  const float* kv_scales;
+  const int32_t* page_table;
+  void* out;
+  float* lse;
+  float* part_o;    // [n_slots, head_block, 512]
+  float* part_lse;  // [n_slots, head_block]
+  const int32_t* unit_seg;
+  const Segment* segs;
+  int H, max_pages, S, W, head_block, out_fp32;
+  float scale_log2;  // softmax_scale * log2(e)
+};
+
+struct CombineParams {
+  const CombineItem* items;
+  const float* part_o;
+  const float* part_lse;
+  void* out;
+  float* lse;
+  int H, head_block, out_fp32;
+};
+
+// One-time per-process kernel attribute setup (large dynamic LDS).
+hipError_t init_kernels();
+// waves in {1, 2, 4}; grid = number of work units.
+hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream);
+hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t stream);
+
+}  // namespace omniattn

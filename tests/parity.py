@@ -1,0 +1,78 @@
+"""Shared helpers for the GPU parity tests: run the HIP library and the CPU
+oracle on the same seeded inputs and compare element by element."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2511_22481_amd as oa
+
+# Tolerances of the decode path against the fp64 oracle.
+MAX_ABS = 2e-2
+REL_L2 = {"bf16": 1e-2, "fp8": 5e-2}
+LSE_ABS = 1e-3
+
+
+def to_device(inp, device="cuda"):
+    inp.q = inp.q.to(device)
+    inp.kv_cache = inp.kv_cache.to(device)
+    if inp.kv_scales is not None:
+        inp.kv_scales = inp.kv_scales.to(device)
+    inp.page_table = inp.page_table.to(device)
+    inp.seq_lens = inp.seq_lens.to(device)
+    return inp
+
+
+def run_gpu(inp, out_dtype=None, num_splits_hint=0, plan=None):
+    out, lse, plan = oa.decode(inp.q, inp.kv_cache, inp.kv_scales, inp.page_table,
+                               inp.seq_lens_host, inp.sink, inp.window, inp.softmax_scale,
+                               out_dtype=out_dtype, num_splits_hint=num_splits_hint, plan=plan)
+    torch.cuda.synchronize()
+    return out, lse, plan
+
+
+def run_oracle(inp, pairs=None):
+    return oracle.oracle_decode(inp.q, inp.kv_cache, inp.kv_scales, inp.page_table,
+                                inp.seq_lens_host, inp.sink, inp.window, inp.softmax_scale,
+                                kv_dtype=inp.kv_dtype, pairs=pairs)
+
+
+def errors(out_gpu, lse_gpu, out_ref, lse_ref):
+    """-> dict(max_abs, rel_l2, worst_row_rel_l2, lse_abs); NaN/inf must match exactly."""
+    g = out_gpu.detach().float().cpu().numpy().astype(np.float64).reshape(out_ref.shape)
+    lg = lse_gpu.detach().float().cpu().numpy().astype(np.float64).reshape(lse_ref.shape)
+    assert np.array_equal(np.isnan(g), np.isnan(out_ref)), "NaN pattern of out differs"
+    fin = np.isfinite(lse_ref)
+    assert np.array_equal(lg[~fin], lse_ref[~fin]) or np.array_equal(
+        np.isnan(lg[~fin]), np.isnan(lse_ref[~fin])), "non-finite lse differs"
+    ok = ~np.isnan(out_ref)
+    d = np.where(ok, g - out_ref, 0.0)
+    ref = np.where(ok, out_ref, 0.0)
+    num = np.sqrt((d ** 2).sum())
+    den = np.sqrt((ref ** 2).sum())
+    rows_num = np.sqrt((d ** 2).sum(-1))
+    rows_den = np.sqrt((ref ** 2).sum(-1))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        row_rel = np.where(rows_den > 0, rows_num / rows_den, rows_num)
+    return {
+        "max_abs": float(np.abs(d).max()) if d.size else 0.0,
+        "rel_l2": float(num / den) if den > 0 else float(num),
+        "worst_row_rel_l2": float(row_rel.max()) if row_rel.size else 0.0,
+        "lse_abs": float(np.abs(lg[fin] - lse_ref[fin]).max()) if fin.any() else 0.0,
+    }
+
+
+def assert_parity(inp, out_gpu, lse_gpu, pairs=None, rel_l2=None, row_rel_l2=None, what=""):
+    out_ref, lse_ref = run_oracle(inp, pairs=pairs)
+    if pairs is not None:
+        idx = torch.as_tensor(np.asarray(pairs), dtype=torch.long)
+        out_gpu = out_gpu[idx[:, 0], idx[:, 1]]
+        lse_gpu = lse_gpu[idx[:, 0], idx[:, 1]]
+    e = errors(out_gpu, lse_gpu, out_ref, lse_ref)
+    tol = REL_L2[inp.kv_dtype] if rel_l2 is None else rel_l2
+    msg = f"{what} {e}"
+    assert e["max_abs"] <= MAX_ABS, msg
+    assert e["rel_l2"] <= tol, msg
+    assert e["lse_abs"] <= LSE_ABS, msg
+    if row_rel_l2 is not None:
+        assert e["worst_row_rel_l2"] <= row_rel_l2, msg
+    return e
