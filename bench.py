@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse MLA decode hot path on one MI355X.
+
+A step = one omniattn_decode call (main kernel + combine) over one batch of the
+DeepSeek-R1-shaped workload (B=64, H=128, L=32768, S=128, W=2048, bf16 paged
+cache with shuffled 128-token pages).  Inputs are synthetic, seeded and already
+resident in HBM; the plan is built once before the timed region.  To keep the
+"HBM" figure honest the timed steps rotate over several independent
+(q, cache, page table) sets whose touched KV together exceeds the 256 MB
+last-level cache.
+
+Prints ONE JSON line: retained KV tokens/s, ms per step, the roofline of the
+dominant kernel (live HIP-event timing on the launch stream), and the fp64 CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+WORKLOAD = "r1_b64_32k"
+
+
+def algorithmic_bytes(retained_tokens, batch, heads, kv_dtype):
+    """Bytes one decode must move: each retained latent row once, Q once, bf16 O once, lse."""
+    per_tok = 1152 if kv_dtype == "bf16" else 580
+    per_seq = heads * 576 * 2 + heads * 512 * 2 + heads * 4
+    return retained_tokens * per_tok + batch * per_seq
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--sets", type=int, default=3, help="independent input sets rotated over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default=WORKLOAD)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by batch with no "
+              "exchange step; see DESIGN.md). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_22481_amd as oa
+    from workloads import get_config, make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the decode library has no CPU path.", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = get_config(args.workload)
+
+    sets = []
+    for i in range(args.sets):
+        inp = make_inputs(cfg, device=dev, seed_offset=1000 * i)
+        sets.append(inp)
+    inp0 = sets[0]
+    fp8 = cfg.kv_dtype == "fp8"
+    plan = oa.omniattn_plan(inp0.seq_lens_host, batch=inp0.batch, num_heads=inp0.heads,
+                            max_pages_per_seq=inp0.max_pages, num_pages=inp0.num_pages,
+                            sink=inp0.sink, window=inp0.window, softmax_scale=inp0.softmax_scale,
+                            kv_dtype=oa.FP8_E4M3 if fp8 else oa.BF16, out_dtype=oa.BF16)
+    out = torch.empty((inp0.batch, inp0.heads, 512), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((inp0.batch, inp0.heads), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        s = sets[i % len(sets)]
+        oa.omniattn_decode(plan, s.q, s.kv_cache, s.kv_scales, s.page_table, out, lse, ws, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # whole-step timing: K steps between two events on the launch stream
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(args.steps):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = max(ev_ms, 0.0) / args.steps
+
+    # dominant kernel alone: HIP events recorded by the library on the launch stream
+    # right before and after the main kernel of every step (torch's events only see
+    # torch's current stream, so plain HIP events are used).
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                        ctypes.c_void_p]
+    n_ev = min(args.steps, 200)
+    evs = []
+    for _ in range(3 * n_ev):
+        e = ctypes.c_void_p()
+        if hip.hipEventCreate(ctypes.byref(e)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        evs.append(e)
+    for i in range(n_ev):
+        s = sets[i % len(sets)]
+        oa.omniattn_decode_timed(plan, s.q, s.kv_cache, s.kv_scales, s.page_table, out, lse, ws,
+                                 stream, evs[3 * i], evs[3 * i + 1], evs[3 * i + 2])
+    torch.cuda.synchronize()
+    main_tot = comb_tot = 0.0
+    for i in range(n_ev):
+        ms = ctypes.c_float()
+        hip.hipEventElapsedTime(ctypes.byref(ms), evs[3 * i], evs[3 * i + 1])
+        main_tot += ms.value
+        hip.hipEventElapsedTime(ctypes.byref(ms), evs[3 * i + 1], evs[3 * i + 2])
+        comb_tot += ms.value
+    main_ms = main_tot / n_ev
+    combine_ms = comb_tot / n_ev
+    for e in evs:
+        hip.hipEventDestroy(e)
+
+    retained = plan.retained_tokens
+    alg_bytes = algorithmic_bytes(retained, inp0.batch, inp0.heads, cfg.kv_dtype)
+    value = retained / (ms_per_step * 1e-3)
+    kern_ms = main_ms
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "sparse MLA decode: retained KV tokens/s + HBM GB/s, B=64 ctx 32k",
+        "value": value,
+        "unit": "retained KV tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if not fp8 else "fp8_e4m3 cache, bf16 mfma",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: B={cfg.batch} H={cfg.heads} L={cfg.ctx} S={cfg.sink} "
+                        f"W={cfg.window} {cfg.kv_dtype} paged(128, shuffled)",
+            "retained_tokens": retained,
+            "algorithmic_bytes": alg_bytes,
+            "algorithmic_GBps_step": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+            "input_sets_rotated": len(sets),
+            "work_units": plan.num_units,
+            "partials": plan.num_partials,
+            "head_block": plan.head_block,
+            "wall_ms_per_step": wall_ms / args.steps,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "decode_kernel (main pass; combine excluded)",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": None,
+            "kernel_ms": kern_ms,
+            "combine_ms": combine_ms,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        # bounded sample: the first sequences of the same workload, all heads
+        nb = 2 if cfg.batch >= 2 else 1
+        small = make_inputs(cfg, device="cpu", batch=nb)
+        t0 = time.perf_counter()
+        oracle.oracle_decode(small.q, small.kv_cache, small.kv_scales, small.page_table,
+                             small.seq_lens_host, small.sink, small.window, small.softmax_scale,
+                             kv_dtype=small.kv_dtype)
+        dt = time.perf_counter() - t0
+        toks = sum(min(L, min(small.sink, L) + min(small.window, L)) if small.sink + small.window < L
+                   else L for L in small.seq_lens_host)
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count()
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        result["cpu_baseline"] = {
+            "value": toks / dt,
+            "unit": "retained KV tokens/s",
+            "cores": cores,
+            "kind": "oracle",
+            "sample": f"first {nb} of {cfg.batch} sequences, all {cfg.heads} heads "
+                      f"({toks} retained tokens, {dt:.1f} s, fp64 C + OpenMP)",
+        }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

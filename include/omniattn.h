@@ -147,6 +147,19 @@ int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_c
                     const float* kv_scales, const int32_t* page_table, void* out,
                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Same as omniattn_decode, and additionally records caller-owned HIP events
+ * (hipEvent_t cast to void*, any may be NULL) on `hip_stream`: `ev_begin` before
+ * the main kernel, `ev_main_end` after it, `ev_end` after the combine kernel
+ * (recorded right after `ev_main_end` when the plan needs no combine).  For
+ * benchmarks that report the main kernel's duration on its own; nothing is
+ * allocated and nothing synchronises.
+ */
+int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
+                          const float* kv_scales, const int32_t* page_table, void* out,
+                          float* lse, void* workspace, size_t workspace_bytes, void* hip_stream,
+                          void* ev_begin, void* ev_main_end, void* ev_end);
+
 const char* omniattn_strerror(int code);
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char* omniattn_last_hip_error(void);

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     omniattn_plan,
     omniattn_plan_host,
     omniattn_decode,
+    omniattn_decode_timed,
     decode,
     lib_path,
     load_library,

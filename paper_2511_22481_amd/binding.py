@@ -67,6 +67,8 @@ def load_library():
                                              ctypes.POINTER(ctypes.c_int32)]
     lib.omniattn_decode.restype = ctypes.c_int
     lib.omniattn_decode.argtypes = [P, P, P, P, P, P, P, P, ctypes.c_size_t, P]
+    lib.omniattn_decode_timed.restype = ctypes.c_int
+    lib.omniattn_decode_timed.argtypes = [P, P, P, P, P, P, P, P, ctypes.c_size_t, P, P, P, P]
     lib.omniattn_strerror.restype = ctypes.c_char_p
     lib.omniattn_strerror.argtypes = [ctypes.c_int]
     lib.omniattn_last_hip_error.restype = ctypes.c_char_p
@@ -175,6 +177,16 @@ def omniattn_decode(plan, q, kv_cache, kv_scales, page_table, out, lse, workspac
     _check(load_library().omniattn_decode(
         plan.handle, _ptr(q), _ptr(kv_cache), _ptr(kv_scales), _ptr(page_table), _ptr(out),
         _ptr(lse), _ptr(workspace), ws_bytes, ctypes.c_void_p(stream.cuda_stream)))
+
+
+def omniattn_decode_timed(plan, q, kv_cache, kv_scales, page_table, out, lse, workspace, stream,
+                          ev_begin, ev_main_end, ev_end):
+    """omniattn_decode plus three caller-owned hipEvent_t handles (ints or None)."""
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load_library().omniattn_decode_timed(
+        plan.handle, _ptr(q), _ptr(kv_cache), _ptr(kv_scales), _ptr(page_table), _ptr(out),
+        _ptr(lse), _ptr(workspace), ws_bytes, ctypes.c_void_p(stream.cuda_stream),
+        ev_begin, ev_main_end, ev_end))
 
 
 def decode(q, kv_cache, kv_scales, page_table, seq_lens_host, sink, window, softmax_scale,

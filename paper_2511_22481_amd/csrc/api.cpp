@@ -165,6 +165,14 @@ int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t til
 int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
                     const float* kv_scales, const int32_t* page_table, void* out, float* lse,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return omniattn_decode_timed(plan, q, kv_cache, kv_scales, page_table, out, lse, workspace,
+                               workspace_bytes, hip_stream, nullptr, nullptr, nullptr);
+}
+
+int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
+                          const float* kv_scales, const int32_t* page_table, void* out,
+                          float* lse, void* workspace, size_t workspace_bytes, void* hip_stream,
+                          void* ev_begin, void* ev_main_end, void* ev_end) {
   if (!plan || !q || !kv_cache || !page_table || !out || !lse) return OMNIATTN_EINVAL;
   if (!plan->on_device) return OMNIATTN_EINVAL;
   const HostPlan& hp = plan->hp;
@@ -195,7 +203,9 @@ int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_c
   dp.head_block = hp.head_block;
   dp.out_fp32 = hp.prob.out_dtype == OMNIATTN_FP32;
   dp.scale_log2 = hp.prob.softmax_scale * 1.4426950408889634f;
+  if (ev_begin) OA_HIP(hipEventRecord((hipEvent_t)ev_begin, stream));
   OA_HIP(launch_decode(dp, hp.waves, fp8, (int)hp.unit_seg.size() - 1, stream));
+  if (ev_main_end) OA_HIP(hipEventRecord((hipEvent_t)ev_main_end, stream));
 
   if (!hp.combine.empty()) {
     CombineParams cp;
@@ -209,6 +219,7 @@ int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_c
     cp.out_fp32 = dp.out_fp32;
     OA_HIP(launch_combine(cp, (int)hp.combine.size(), stream));
   }
+  if (ev_end) OA_HIP(hipEventRecord((hipEvent_t)ev_end, stream));
   return OMNIATTN_OK;
 }
 

@@ -43,15 +43,26 @@ constexpr int kTileBytes = kTile * kRowBytes; // 73,728
 constexpr int kScaleBytes = kTile * 4;        // per-token fp32 scales of one tile (fp8 cache)
 constexpr int kLdsBytes = 2 * kTileBytes + 2 * kScaleBytes + 16;  // + redo flag
 
-// 16-byte chunk c of LDS row r is stored at chunk position c ^ swz(r).
-// swz permutes the three bits of (r >> 1) & 7 so that
-//  - 16 consecutive rows at one chunk index (the MFMA A-operand gather of
-//    K rows) land in 16 different 16-byte bank groups, and
-//  - 4 consecutive rows x 64 bytes (one transposing read of V) land in four
-//    different quarters of the 64 banks.
-__device__ __forceinline__ int swz(int r) {
-  int x = (r >> 1) & 7;
-  return ((x & 1) << 2) | (x >> 1);
+// LDS layout of one 64-token tile (73,728 bytes).  A token row is 72 chunks of
+// 16 bytes: chunks 0..63 (the 512 value dims) and 64..71 (the 64 rope dims).
+//   main part: row r at r * 1024; chunk c < 64 sits at position c ^ swz_main(r)
+//   tail part: at kTailBase + r * 128; chunk 64 + c sits at position c ^ swz_tail(r)
+// Splitting the row this way makes one direct global->LDS load instruction
+// (64 lanes x 16 bytes = 1024 contiguous LDS bytes) fill exactly one main row,
+// so a lane's global offset is a lane constant plus a per-instruction constant.
+// The XOR swizzles make both read patterns bank-conflict free: 16 consecutive
+// rows at one chunk index (A-operand gather of K rows) land in 16 different
+// 16-byte bank groups, and 4 consecutive rows x 64 bytes (one transposing read
+// of V) land in the four quarters of the 64 banks.
+constexpr int kMainRowBytes = 1024;
+constexpr int kTailRowBytes = 128;
+constexpr int kTailBase = kTile * kMainRowBytes;  // 65,536
+__host__ __device__ constexpr int swz_main(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+__host__ __device__ constexpr int swz_tail(int r) { return (r >> 1) & 7; }
+// byte offset of chunk c (0..71) of row r inside a tile buffer
+__device__ __forceinline__ uint32_t lds_chunk(int r, int c) {
+  return c < 64 ? r * kMainRowBytes + ((c ^ swz_main(r)) << 4)
+                : kTailBase + r * kTailRowBytes + (((c - 64) ^ swz_tail(r)) << 4);
 }
 
 __device__ __forceinline__ bool retained(int j, int L, int S, int W) {
@@ -97,31 +108,28 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const uint32_t lds_flag = lds_scales + 2 * kScaleBytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
   const int n32 = lane & 31;  // head within the wave's 32 (B / C column)
   const int g = lane >> 5;    // k-group of the MFMA operands
 
   // ---- per-lane LDS read offsets (relative to a tile buffer) ----
-  // QK^T A operand: token row n32 (+32 per block), 16-byte chunk (2 ks + g) ^ swz(row).
-  const int fq = swz(n32);
-  uint32_t a_off[4];
-#pragma unroll
-  for (int b = 0; b < 4; ++b) a_off[b] = n32 * kRowBytes + (((2 * b + g) ^ fq) << 4);
+  // QK^T A operand: token row n32 (+32 per block), chunk 2 ks + g.  For ks < 32 the
+  // chunk position is ((2 (ks & 7) + g) ^ swz) + 16 (ks >> 3); since 2 (ks & 7) has
+  // bit 0 clear, the byte offset is a_main ^ ((ks & 7) << 5) plus a constant.
+  const uint32_t a_main = n32 * kMainRowBytes + ((g ^ swz_main(n32)) << 4);
+  const uint32_t a_tail = kTailBase + n32 * kTailRowBytes + ((g ^ swz_tail(n32)) << 4);
   // PV A operand (V^T): each 16-lane group reads a 4-token x 16-column block transposed.
+  // Lane row = 16 th + 8 hi + 4 g + (i16 >> 2); chunk = 4 cb + c_lane.
   const int i16 = lane & 15;
-  const int vrow = g * 4 + (i16 >> 2);  // + 16 per token half (+ 8 for the upper k-slots)
   const int c_lane = ((lane >> 4) & 1) * 2 + ((i16 & 3) >> 1);
   const int half8 = (i16 & 1) * 8;
-  uint32_t v_off[2][2];  // [upper k-slots][column-block parity]
+  uint32_t v_off[2][4];  // [upper k-slots][cb & 3]; add (cb >> 2) * 256 + th * 16 rows
 #pragma unroll
   for (int hi = 0; hi < 2; ++hi) {
-    int r = vrow + hi * 8;
-    int f = swz(r);
+    const int r = hi * 8 + g * 4 + (i16 >> 2);
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      int c = (par * 4 + c_lane) ^ f;  // chunk index inside the aligned group of 8
-      v_off[hi][par] = r * kRowBytes + (c << 4) + half8;
-    }
+    for (int cl = 0; cl < 4; ++cl)
+      v_off[hi][cl] = r * kMainRowBytes + (((cl * 4 + c_lane) ^ swz_main(r)) << 4) + half8;
   }
 
   const int unit = blockIdx.x;
@@ -156,37 +164,46 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       const uint32_t lbase = lds0 + buf * kTileBytes;
       if constexpr (!FP8) {
         const uint8_t* gbase = p.kv + ((size_t)page * kPage + slot0) * kRowBytes;
-        constexpr int rows_per_wave = kTile / WAVES;
-        constexpr int n_instr = rows_per_wave * kChunksPerRow / 64;
+        constexpr int rows_per_wave = kTile / WAVES;  // 16, 32 or 64: a multiple of 16
         const int row_w0 = wave * rows_per_wave;
         if (full) {
+          // The per-lane offsets below are loop invariant; recomputing them (an XOR and a
+          // shift) is cheaper than keeping 18 of them alive across the MFMA loops, so the
+          // lane id is passed through an opaque move that stops the compiler hoisting them.
+          uint32_t l = lane;
+          asm volatile("" : "+v"(l));
+          // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
 #pragma unroll
-          for (int j = 0; j < n_instr; ++j) {
-            int pidx = j * 64 + lane;             // chunk position within the wave's rows
-            int r = pidx / kChunksPerRow;
-            int cpos = pidx - r * kChunksPerRow;  // chunk position inside the LDS row
-            int row = row_w0 + r;
-            int csrc = cpos ^ swz(row);           // source chunk that belongs there
-            const uint8_t* src = gbase + row * kRowBytes + (csrc << 4);
-            uint32_t dst = lbase + (row_w0 * kChunksPerRow + j * 64) * 16;  // wave-uniform
+          for (int j = 0; j < rows_per_wave; ++j) {
+            const int row = row_w0 + j;
+            const uint32_t off = row * kRowBytes + ((l ^ swz_main(j)) << 4);
             __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1)))*)src,
-                (void __attribute__((address_space(3)))*)(uintptr_t)dst, 16, 0, 0);
+                (const void __attribute__((address_space(1)))*)(gbase + off),
+                (void __attribute__((address_space(3)))*)(uintptr_t)(lbase + row * kMainRowBytes),
+                16, 0, 0);
+          }
+          // tail part: one instruction per 8 rows; lane l fetches row l / 8, rope chunk (l & 7) ^ swz
+#pragma unroll
+          for (int k = 0; k < rows_per_wave / 8; ++k) {
+            const uint32_t r8 = 8 * k + (l >> 3);  // row within the wave's share (row_w0 is a multiple of 16)
+            const uint32_t off = (row_w0 + r8) * kRowBytes + ((64 + ((l & 7) ^ swz_tail(r8))) << 4);
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1)))*)(gbase + off),
+                (void __attribute__((address_space(3)))*)(uintptr_t)(lbase + kTailBase +
+                                                                     (row_w0 + 8 * k) * kTailRowBytes),
+                16, 0, 0);
           }
         } else {
           // partial tile: rows outside the retained set are zero-filled, never loaded
           // (their contents are unspecified and 0 * NaN would poison the PV product)
 #pragma unroll 1
-          for (int j = 0; j < n_instr; ++j) {
-            int pidx = j * 64 + lane;
-            int r = pidx / kChunksPerRow;
-            int cpos = pidx - r * kChunksPerRow;
-            int row = row_w0 + r;
-            int csrc = cpos ^ swz(row);
+          for (int ci = lane; ci < rows_per_wave * kChunksPerRow; ci += 64) {
+            const int r = ci / kChunksPerRow;
+            const int c = ci - r * kChunksPerRow;
+            const int row = row_w0 + r;
             u32x4 v = {0, 0, 0, 0};
-            if (retained(pos0 + row, L, p.S, p.W))
-              v = *(const u32x4*)(gbase + row * kRowBytes + (csrc << 4));
-            *LDS_PTR(u32x4, lbase + (row_w0 * kChunksPerRow + pidx) * 16) = v;
+            if (retained(pos0 + row, L, p.S, p.W)) v = *(const u32x4*)(gbase + row * kRowBytes + (c << 4));
+            *LDS_PTR(u32x4, lbase + lds_chunk(row, c)) = v;
           }
         }
       } else {
@@ -221,9 +238,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               w[2 * k] = __builtin_bit_cast(uint32_t, blo);
               w[2 * k + 1] = __builtin_bit_cast(uint32_t, bhi);
             }
-            int f = swz(row);
-            *LDS_PTR(u32x4, lbase + row * kRowBytes + (((2 * cc) ^ f) << 4)) = u32x4{w[0], w[1], w[2], w[3]};
-            *LDS_PTR(u32x4, lbase + row * kRowBytes + (((2 * cc + 1) ^ f) << 4)) = u32x4{w[4], w[5], w[6], w[7]};
+            *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc)) = u32x4{w[0], w[1], w[2], w[3]};
+            *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc + 1)) = u32x4{w[4], w[5], w[6], w[7]};
           }
         }
         if (tid < kTile) {
@@ -269,14 +285,17 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         // The MFMAs are volatile assembly, which the scheduler does not move loads
         // across, so the LDS reads are software-pipelined by hand: each fragment is
         // requested kDepth MFMAs ahead of its use.
-        auto load_k = [&](uint32_t blk, int ks) -> bf16x8 {
-          return *LDS_PTR(bf16x8, blk + a_off[ks & 3] + (ks >> 2) * 128);
+        auto load_k = [&](int tb, int ks) -> bf16x8 {
+          if (ks < 32)
+            return *LDS_PTR(bf16x8, tb_base + (a_main ^ ((ks & 7) << 5)) + (ks >> 3) * 256 +
+                                        tb * 32 * kMainRowBytes);
+          return *LDS_PTR(bf16x8, tb_base + (a_tail ^ ((ks - 32) << 5)) + tb * 32 * kTailRowBytes);
         };
-        auto load_v = [&](uint32_t blk, int j) -> bf16x8 {  // j = th * 16 + cb
+        auto load_v = [&](int tb, int j) -> bf16x8 {  // j = th * 16 + cb
           const int th = j >> 4, cb = j & 15;
-          uint32_t base = blk + th * 16 * kRowBytes + (cb >> 1) * 128;
-          s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + v_off[0][cb & 1]));
-          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + v_off[1][cb & 1]));
+          const uint32_t base = tb_base + (tb * 32 + th * 16) * kMainRowBytes + (cb >> 2) * 256;
+          s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + v_off[0][cb & 3]));
+          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + v_off[1][cb & 3]));
           return __builtin_bit_cast(
               bf16x8, (__attribute__((ext_vector_type(8))) short){lo[0], lo[1], lo[2], lo[3], hi[0],
                                                                   hi[1], hi[2], hi[3]});
@@ -287,10 +306,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 
 #pragma unroll 1
         for (int tb = 0; tb < kTile / 32; ++tb) {
-          const uint32_t blk = tb_base + tb * 32 * kRowBytes;
           bf16x8 kf[kDepth], vf[kDepth];
 #pragma unroll
-          for (int d = 0; d < kDepth; ++d) kf[d] = load_k(blk, d);
+          for (int d = 0; d < kDepth; ++d) kf[d] = load_k(tb, d);
 
           // ---- S^T = K . Q^T ----
           f32x16 s;
@@ -298,8 +316,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           for (int ks = 0; ks < kNK; ++ks) {
             if (ks == 0) mfma_s_first(s, kf[ks % kDepth], qf[ks]);
             else mfma_s(s, kf[ks % kDepth], qf[ks]);
-            if (ks + kDepth < kNK) kf[ks % kDepth] = load_k(blk, ks + kDepth);
-            else if constexpr (!MAX_ONLY) vf[(ks + kDepth - kNK) % kDepth] = load_v(blk, ks + kDepth - kNK);
+            if (ks + kDepth < kNK) kf[ks % kDepth] = load_k(tb, ks + kDepth);
+            else if constexpr (!MAX_ONLY) vf[(ks + kDepth - kNK) % kDepth] = load_v(tb, ks + kDepth - kNK);
           }
           settle_s(s);
 
@@ -347,7 +365,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 #pragma unroll
           for (int j = 0; j < kNV; ++j) {
             mfma_o(acc[j & 15], vf[j % kDepth], pf[j >> 4]);
-            if (j + kDepth < kNV) vf[j % kDepth] = load_v(blk, j + kDepth);
+            if (j + kDepth < kNV) vf[j % kDepth] = load_v(tb, j + kDepth);
           }
         }
       }
