@@ -40,8 +40,34 @@ def build(force=True, verbose=False):
                         if "packed-fp32-ops" not in l))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed")
+    check_generated_code(verbose)
     return LIB
 
 
+def check_generated_code(verbose=False):
+    """Emit the device assembly of the kernels once more and run the static hazard
+    check on it (see check_isa.py); raises if compiler-inserted code reads an MFMA
+    result too early."""
+    import tempfile
+    from .check_isa import check
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "decode_kernels.s")
+        cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Wno-unused-command-line-argument", "--cuda-device-only", "-S", "-x", "hip",
+               os.path.join(CSRC, "decode_kernels.hip"), "-o", out]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc -S failed:\n" + res.stderr[-2000:])
+        problems = check(open(out).read())
+    if problems:
+        raise RuntimeError("generated code reads MFMA results too early:\n" + "\n".join(problems[:20]))
+    if verbose:
+        print("ISA hazard check: ok")
+
+
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    sys.path.insert(0, os.path.dirname(HERE))
+    from paper_2511_22481_amd.build import build as _b
+    print(_b(verbose=True))

@@ -1,0 +1,83 @@
+"""Static check of the generated gfx950 code for hazards the compiler cannot see.
+
+The decode kernel issues its MFMAs from inline assembly, so the compiler's hazard
+recognizer does not know that the registers they write are not readable for a
+number of wait states (12 after an 8-pass MFMA for a vector-ALU read, more for a
+memory instruction).  Our own code supplies the `s_nop`s where it reads results;
+this check guards against compiler-inserted code (register moves, spills) that
+touches an MFMA destination too early.  It walks each decode kernel's
+instruction stream in program order, conservatively assuming fall-through, and
+fails the build if a non-MFMA instruction names a register of an MFMA
+destination fewer than `MIN_STATES` wait states after that MFMA.
+"""
+import re
+import sys
+
+VALU_STATES = 12  # vector-ALU read of an 8-pass MFMA result
+MEM_STATES = 19   # memory / LDS / export instruction reading it
+MIN_STATES = VALU_STATES
+_MEM_PREFIXES = ("scratch_", "global_", "buffer_", "flat_", "ds_")
+
+_REG_RANGE = re.compile(r"\b([av])\[(\d+):(\d+)\]")
+_REG_ONE = re.compile(r"\b([av])(\d+)\b")
+
+
+def _regs(text):
+    out = set()
+    for k, lo, hi in _REG_RANGE.findall(text):
+        out.update((k, i) for i in range(int(lo), int(hi) + 1))
+    for k, i in _REG_ONE.findall(_REG_RANGE.sub(" ", text)):
+        out.add((k, int(i)))
+    return out
+
+
+def check(asm_text, kernel_filter="decode_kernel"):
+    """Returns a list of violation strings (empty = fine)."""
+    problems = []
+    in_kernel = False
+    pending = {}  # register -> wait states elapsed since the MFMA that writes it
+    for lineno, raw in enumerate(asm_text.splitlines(), 1):
+        line = raw.split(";")[0].strip()
+        if not line:
+            continue
+        if line.endswith(":") and not line.startswith("."):
+            in_kernel = kernel_filter in line
+            pending = {}
+            continue
+        if not in_kernel or line.startswith(".") or line.endswith(":"):
+            continue
+        op, _, rest = line.partition(" ")
+        if op.startswith("v_mfma"):
+            operands = [x.strip() for x in rest.split(",")]
+            dst = _regs(operands[0])
+            srcs = _regs(",".join(operands[1:3]))  # A and B must be readable; C may chain
+            for r in srcs:
+                if r in pending and pending[r] < MIN_STATES:
+                    problems.append(f"line {lineno}: MFMA reads {r} {pending[r]} states after an MFMA wrote it: {line}")
+            for r in list(pending):
+                pending[r] += 1
+            for r in dst:
+                pending[r] = 0
+            continue
+        states = 1
+        if op == "s_nop":
+            states = int(rest.strip()) + 1
+        else:
+            need = MEM_STATES if op.startswith(_MEM_PREFIXES) else VALU_STATES
+            for r in _regs(rest):
+                if r in pending and pending[r] < need:
+                    problems.append(f"line {lineno}: {pending[r]} wait states after MFMA write of "
+                                    f"{r[0]}{r[1]}: {line}")
+        for r in list(pending):
+            pending[r] += states
+            if pending[r] >= 64:
+                del pending[r]
+        if op in ("s_endpgm",):
+            in_kernel = False
+    return problems
+
+
+if __name__ == "__main__":
+    probs = check(open(sys.argv[1]).read())
+    print("\n".join(probs[:40]) or "ok")
+    sys.exit(1 if probs else 0)

@@ -1,20 +1,21 @@
 // gfx950 kernels for sparse MLA decode over the OmniAttn retained set
 // (paper section 3.2.1: softmax(q K_M^T * scale) V_M with M = sinks + recents).
 //
-// Main kernel, one work group per work unit, WAVES waves, each wave owning 32
-// heads and the full 512-wide output of those heads:
-//   a3  retained 64-token tile -> LDS by direct global->LDS 16-byte loads
-//       (double buffered), rows XOR-swizzled so that both later read patterns
-//       are bank-conflict free;
+// Main kernel: one work group per work unit, WAVES waves, one wave per SIMD; each
+// wave owns 32 heads and the full 512-wide output row of those heads.
+//   a3  retained 32-token tiles stream into a ring of four LDS stages by direct
+//       global->LDS 16-byte loads, two tiles ahead of the compute;
 //   a4  S^T[token, head] = K_tile . Q^T on 32x32x16 bf16 MFMA, Q held in
 //       registers as the B operand for the whole segment;
 //   a5  positions outside the retained set get -inf (partial tiles only);
-//   a6  online softmax per head: a lane holds 16 tokens of one head per
-//       32-token block, its partner lane (lane ^ 32) the other 16;
+//   a6  softmax against a per-segment reference (see kRefSlack): a lane holds 16
+//       tokens of one head, its partner lane (lane ^ 32) the other 16;
 //   a7  O^T[col, head] += V^T . P^T on the same MFMA; the C layout of S^T is
 //       exactly the B layout P^T needs, so P never leaves registers; V^T comes
-//       from the same LDS tile through transposing LDS reads;
-//   a8  normalise, write bf16/fp32 output + lse, or an fp32 partial.
+//       from the same LDS tile through transposing LDS reads.  The PV MFMAs of
+//       tile i-1 are issued interleaved with the softmax arithmetic of tile i;
+//   a8  normalise, transpose through LDS, write bf16/fp32 rows + lse, or an fp32
+//       partial row.
 // Combine kernel (a9): merges the partials of sequences that were split.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,38 +33,44 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 #define LDS_PTR(T, byte_off) ((__attribute__((address_space(3))) T*)(uintptr_t)(byte_off))
 
-constexpr int kRowBytes = kQK * 2;            // one token row in LDS (bf16)
-constexpr int kChunksPerRow = kRowBytes / 16; // 72
-constexpr int kTileBytes = kTile * kRowBytes; // 73,728
-constexpr int kScaleBytes = kTile * 4;        // per-token fp32 scales of one tile (fp8 cache)
-constexpr int kLdsBytes = 2 * kTileBytes + 2 * kScaleBytes + 16;  // + redo flag
+constexpr int kRowBytes = kQK * 2;             // one token row in global memory (bf16)
+constexpr int kChunksPerRow = kRowBytes / 16;  // 72
 
-// LDS layout of one 64-token tile (73,728 bytes).  A token row is 72 chunks of
+// LDS layout of one 32-token stage (36,864 bytes).  A token row is 72 chunks of
 // 16 bytes: chunks 0..63 (the 512 value dims) and 64..71 (the 64 rope dims).
 //   main part: row r at r * 1024; chunk c < 64 sits at position c ^ swz_main(r)
 //   tail part: at kTailBase + r * 128; chunk 64 + c sits at position c ^ swz_tail(r)
 // Splitting the row this way makes one direct global->LDS load instruction
 // (64 lanes x 16 bytes = 1024 contiguous LDS bytes) fill exactly one main row,
-// so a lane's global offset is a lane constant plus a per-instruction constant.
+// so a lane's global offset is a lane constant XOR a per-row constant.
 // The XOR swizzles make both read patterns bank-conflict free: 16 consecutive
 // rows at one chunk index (A-operand gather of K rows) land in 16 different
 // 16-byte bank groups, and 4 consecutive rows x 64 bytes (one transposing read
 // of V) land in the four quarters of the 64 banks.
 constexpr int kMainRowBytes = 1024;
 constexpr int kTailRowBytes = 128;
-constexpr int kTailBase = kTile * kMainRowBytes;  // 65,536
+constexpr int kTailBase = kTile * kMainRowBytes;                      // 32,768
+constexpr int kStageBytes = kTile * (kMainRowBytes + kTailRowBytes);  // 36,864
+constexpr int kStages = 4;
+constexpr int kScaleBytes = kTile * 4;  // per-token fp32 scales of one stage (fp8 cache)
+constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16;  // + retry flag
 __host__ __device__ constexpr int swz_main(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 __host__ __device__ constexpr int swz_tail(int r) { return (r >> 1) & 7; }
-// byte offset of chunk c (0..71) of row r inside a tile buffer
+// byte offset of chunk c (0..71) of row r inside a stage
 __device__ __forceinline__ uint32_t lds_chunk(int r, int c) {
   return c < 64 ? r * kMainRowBytes + ((c ^ swz_main(r)) << 4)
                 : kTailBase + r * kTailRowBytes + (((c - 64) ^ swz_tail(r)) << 4);
 }
+
+// Epilogue staging (reuses the stages): per wave 32 head rows of 1024 bytes + 16 pad.
+constexpr int kOutRowBytes = 1024 + 16;
+constexpr int kOutWaveBytes = kHeadsPerWave * kOutRowBytes;  // 33,280; x4 waves fits the stages
 
 __device__ __forceinline__ bool retained(int j, int L, int S, int W) {
   return j < L && (j < S || j >= L - W);
@@ -77,7 +84,7 @@ __device__ __forceinline__ bool retained(int j, int L, int S, int W) {
 // land in the accumulation file and O^T must never leave it.  Wait states the
 // hardware does not interlock are supplied by hand: back-to-back MFMAs that
 // accumulate into the same registers need none; a vector-ALU read of the result
-// of an 8-pass MFMA needs 12 (settle()).
+// of an 8-pass MFMA needs 12 (settle_*()).
 __device__ __forceinline__ void mfma_s_first(f32x16& s, bf16x8 a, bf16x8 b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(a), "v"(b));
 }
@@ -88,34 +95,69 @@ __device__ __forceinline__ void settle_s(f32x16& s) { asm volatile("s_nop 11" : 
 __device__ __forceinline__ void mfma_o(f32x16& acc, bf16x8 a, bf16x8 b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
-__device__ __forceinline__ void settle_o(f32x16& acc) { asm volatile("s_nop 11" : "+a"(acc)); }
+// Every block of the O^T tile at once: nothing may read any of them before this point.
+__device__ __forceinline__ void settle_o(f32x16 (&acc)[kV / 32]) {
+  asm volatile("s_nop 11"
+               : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]),
+                 "+a"(acc[6]), "+a"(acc[7]), "+a"(acc[8]), "+a"(acc[9]), "+a"(acc[10]), "+a"(acc[11]),
+                 "+a"(acc[12]), "+a"(acc[13]), "+a"(acc[14]), "+a"(acc[15]));
+}
 
-// Softmax reference.  exp2(x - r) is evaluated against a per-head reference r
-// that is fixed for a whole segment (the maximum of the segment's first 32-token
-// block), not against a running maximum: softmax is invariant to r, so the only
-// requirement is that exp2 does not overflow.  That removes every rescaling of
-// the 256-register O^T tile from the loop.  If a later logit exceeds r by more
-// than kRefSlack (2^64 headroom below fp32/bf16 overflow even after summing a
-// million terms) the segment is redone once with r = its exact maximum, found
-// by a QK-only pass.
+// Direct global->LDS load of 16 bytes per lane: lane l's bytes land at LDS address
+// lds_base + 16 l (lds_base wave-uniform), read from base + off (base wave-uniform,
+// off per lane).  Written as assembly so that the compiler does not treat it as a
+// store that may alias every later LDS read and drain the whole prefetch before the
+// first read of another stage; completion is awaited explicitly (wait_dma) before
+// the barrier that publishes the tile.
+__device__ __forceinline__ void dma16(const uint8_t* base, uint32_t off, uint32_t lds_base) {
+  // both are wave-uniform by construction; make that visible to the register allocator
+  const uint64_t b = (uint64_t)(uintptr_t)base;
+  const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+  const uint32_t b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+  const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
+  const uint32_t slds = __builtin_amdgcn_readfirstlane(lds_base);
+  uint32_t saved_m0;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %3\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
+      : "v"(off), "s"(sbase), "s"(slds));
+}
+// Wait until at most N of this wave's vector-memory operations are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Softmax reference.  exp2(x - r) is evaluated against a per-head reference r that is
+// fixed for a whole segment (the maximum of the segment's first tile), not against a
+// running maximum: softmax is invariant to r, so the only requirement is that exp2
+// does not overflow.  That keeps every rescaling of the 256-register O^T tile out of
+// the kernel.  The running maximum of all logits is tracked on the side; if some logit
+// exceeded r by more than kRefSlack (2^64: far below fp32/bf16 overflow even after
+// summing a million terms) the work group runs the same segment code a second time
+// with r = that exact maximum, which cannot overflow.
 constexpr float kRefSlack = 64.f;
 
 template <int WAVES, bool FP8>
 __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-  const uint32_t lds0 = (uint32_t)(uintptr_t)lds_raw;  // LDS byte address of buffer 0
-  const uint32_t lds_scales = lds0 + 2 * kTileBytes;
-  const uint32_t lds_flag = lds_scales + 2 * kScaleBytes;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds_raw;  // LDS byte address of stage 0
+  const uint32_t lds_scales = lds0 + kStages * kStageBytes;
+  const uint32_t lds_flag = lds_scales + kStages * kScaleBytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
   const int n32 = lane & 31;  // head within the wave's 32 (B / C column)
   const int g = lane >> 5;    // k-group of the MFMA operands
 
-  // ---- per-lane LDS read offsets (relative to a tile buffer) ----
-  // QK^T A operand: token row n32 (+32 per block), chunk 2 ks + g.  For ks < 32 the
-  // chunk position is ((2 (ks & 7) + g) ^ swz) + 16 (ks >> 3); since 2 (ks & 7) has
-  // bit 0 clear, the byte offset is a_main ^ ((ks & 7) << 5) plus a constant.
+  // ---- per-lane LDS read offsets (relative to a stage) ----
+  // QK^T A operand: token row n32, chunk 2 ks + g.  For ks < 32 the chunk position is
+  // ((2 (ks & 7) + g) ^ swz) + 16 (ks >> 3); since 2 (ks & 7) has bit 0 clear, the byte
+  // offset is a_main ^ ((ks & 7) << 5) plus a constant.
   const uint32_t a_main = n32 * kMainRowBytes + ((g ^ swz_main(n32)) << 4);
   const uint32_t a_tail = kTailBase + n32 * kTailRowBytes + ((g ^ swz_tail(n32)) << 4);
   // PV A operand (V^T): each 16-lane group reads a 4-token x 16-column block transposed.
@@ -123,14 +165,17 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const int i16 = lane & 15;
   const int c_lane = ((lane >> 4) & 1) * 2 + ((i16 & 3) >> 1);
   const int half8 = (i16 & 1) * 8;
-  uint32_t v_off[2][4];  // [upper k-slots][cb & 3]; add (cb >> 2) * 256 + th * 16 rows
+  // Chunk position = ((cb & 3) * 4 + c_lane) ^ swz; the swizzle's upper two bits only touch
+  // the (cb & 3) field, so the byte offset is v_base[hi] ^ ((cb & 3) << 6) + (cb >> 2) * 256.
+  uint32_t v_base[2];  // [upper k-slots]
 #pragma unroll
   for (int hi = 0; hi < 2; ++hi) {
     const int r = hi * 8 + g * 4 + (i16 >> 2);
-#pragma unroll
-    for (int cl = 0; cl < 4; ++cl)
-      v_off[hi][cl] = r * kMainRowBytes + (((cl * 4 + c_lane) ^ swz_main(r)) << 4) + half8;
+    v_base[hi] = r * kMainRowBytes + ((c_lane ^ swz_main(r)) << 4) + half8;
   }
+
+  constexpr int kRowsPerWave = kTile / WAVES;                  // 8, 16 or 32
+  constexpr int kDmaPerTile = kRowsPerWave + kRowsPerWave / 8;  // direct loads per wave and tile
 
   const int unit = blockIdx.x;
   const int seg_lo = p.unit_seg[unit], seg_hi = p.unit_seg[unit + 1];
@@ -145,59 +190,50 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const int n_tiles = sg.tile_hi - sg.tile_lo;
     const int sink_end = p.S < L ? p.S : L;
 
-    // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
-    bf16x8 qf[kQK / 16];
-    {
-      // heads past H (a partly filled wave) read the last real head; their results are never written
-      const uint16_t* qrow = p.q + ((size_t)sg.b * p.H + (head_ok ? head : p.H - 1)) * kQK + g * 8;
-#pragma unroll
-      for (int ks = 0; ks < kQK / 16; ++ks)
-        qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
-    }
+    auto tile_pos = [&](int it) { return tl.logical(sg.tile_lo + it) * kTile; };
+    auto tile_full = [&](int pos0) {
+      return (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L);
+    };
+    // Is tile `it` of this segment fetched by direct loads (whole tile retained, bf16)?
+    auto tile_is_dma = [&](int it) { return !FP8 && tile_full(tile_pos(it)); };
 
-    // ---- tile loader: wave w fills its share of the tile's rows ----
-    auto issue_tile = [&](int ti, int buf) {
-      const int pos0 = tl.logical(ti) * kTile;
-      const int page = p.page_table[(size_t)sg.b * p.max_pages + (pos0 >> 7)];
+    // ---- tile loader: wave w fills rows [w * kRowsPerWave, ...) of stage it & 3 ----
+    auto issue_tile = [&](int it) {
+      const int pos0 = tile_pos(it);
+      const int page = __builtin_amdgcn_readfirstlane(
+          p.page_table[(size_t)sg.b * p.max_pages + (pos0 >> 7)]);
       const int slot0 = pos0 & (kPage - 1);
-      const bool full = (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L);
-      const uint32_t lbase = lds0 + buf * kTileBytes;
+      const bool full = tile_full(pos0);
+      const int stage = it & (kStages - 1);
+      const uint32_t lbase = lds0 + stage * kStageBytes;
+      const int row_w0 = wave * kRowsPerWave;
       if constexpr (!FP8) {
         const uint8_t* gbase = p.kv + ((size_t)page * kPage + slot0) * kRowBytes;
-        constexpr int rows_per_wave = kTile / WAVES;  // 16, 32 or 64: a multiple of 16
-        const int row_w0 = wave * rows_per_wave;
         if (full) {
           // The per-lane offsets below are loop invariant; recomputing them (an XOR and a
-          // shift) is cheaper than keeping 18 of them alive across the MFMA loops, so the
-          // lane id is passed through an opaque move that stops the compiler hoisting them.
+          // shift) is cheaper than keeping them alive across the MFMA loops, so the lane id
+          // is passed through an opaque move that stops the compiler hoisting them.
           uint32_t l = lane;
           asm volatile("" : "+v"(l));
           // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
 #pragma unroll
-          for (int j = 0; j < rows_per_wave; ++j) {
+          for (int j = 0; j < kRowsPerWave; ++j) {
             const int row = row_w0 + j;
-            const uint32_t off = row * kRowBytes + ((l ^ swz_main(j)) << 4);
-            __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1)))*)(gbase + off),
-                (void __attribute__((address_space(3)))*)(uintptr_t)(lbase + row * kMainRowBytes),
-                16, 0, 0);
+            const uint32_t off = row * kRowBytes + ((l ^ swz_main(row)) << 4);
+            dma16(gbase, off, lbase + row * kMainRowBytes);
           }
           // tail part: one instruction per 8 rows; lane l fetches row l / 8, rope chunk (l & 7) ^ swz
 #pragma unroll
-          for (int k = 0; k < rows_per_wave / 8; ++k) {
-            const uint32_t r8 = 8 * k + (l >> 3);  // row within the wave's share (row_w0 is a multiple of 16)
-            const uint32_t off = (row_w0 + r8) * kRowBytes + ((64 + ((l & 7) ^ swz_tail(r8))) << 4);
-            __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1)))*)(gbase + off),
-                (void __attribute__((address_space(3)))*)(uintptr_t)(lbase + kTailBase +
-                                                                     (row_w0 + 8 * k) * kTailRowBytes),
-                16, 0, 0);
+          for (int k = 0; k < kRowsPerWave / 8; ++k) {
+            const uint32_t row = row_w0 + 8 * k + (l >> 3);
+            const uint32_t off = row * kRowBytes + ((64 + ((l & 7) ^ swz_tail(row))) << 4);
+            dma16(gbase, off, lbase + kTailBase + (row_w0 + 8 * k) * kTailRowBytes);
           }
         } else {
           // partial tile: rows outside the retained set are zero-filled, never loaded
           // (their contents are unspecified and 0 * NaN would poison the PV product)
 #pragma unroll 1
-          for (int ci = lane; ci < rows_per_wave * kChunksPerRow; ci += 64) {
+          for (int ci = lane; ci < kRowsPerWave * kChunksPerRow; ci += 64) {
             const int r = ci / kChunksPerRow;
             const int c = ci - r * kChunksPerRow;
             const int row = row_w0 + r;
@@ -210,225 +246,263 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         // fp8 rows: 36 chunks of 16 codes; widen each code exactly to bf16, keep the
         // per-token scale aside (it multiplies the logit and the softmax weight).
         const uint8_t* gbase = p.kv + ((size_t)page * kPage + slot0) * kQK;
-        constexpr int n_chunks = kTile * (kQK / 16);  // 2304
+        constexpr int n_chunks = kTile * (kQK / 16);  // 1152
 #pragma unroll 1
-        for (int c0 = 0; c0 < n_chunks; c0 += WAVES * 64 * 3) {
-          u32x4 raw[3];
+        for (int ci = tid; ci < n_chunks; ci += WAVES * 64) {
+          const int row = ci / (kQK / 16);
+          const int cc = ci - row * (kQK / 16);
+          u32x4 raw = {0, 0, 0, 0};
+          if (full || retained(pos0 + row, L, p.S, p.W)) raw = *(const u32x4*)(gbase + row * kQK + cc * 16);
+          uint32_t w[8];
 #pragma unroll
-          for (int u = 0; u < 3; ++u) {
-            int ci = c0 + u * WAVES * 64 + tid;
-            int row = ci / (kQK / 16);
-            int cc = ci - row * (kQK / 16);
-            raw[u] = u32x4{0, 0, 0, 0};
-            if (full || retained(pos0 + row, L, p.S, p.W))
-              raw[u] = *(const u32x4*)(gbase + row * kQK + cc * 16);
+          for (int k = 0; k < 4; ++k) {
+            f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(raw[k], false);
+            f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(raw[k], true);
+            bf16x2 blo = {(__bf16)lo.x, (__bf16)lo.y};
+            bf16x2 bhi = {(__bf16)hi.x, (__bf16)hi.y};
+            w[2 * k] = __builtin_bit_cast(uint32_t, blo);
+            w[2 * k + 1] = __builtin_bit_cast(uint32_t, bhi);
           }
-#pragma unroll
-          for (int u = 0; u < 3; ++u) {
-            int ci = c0 + u * WAVES * 64 + tid;
-            int row = ci / (kQK / 16);
-            int cc = ci - row * (kQK / 16);
-            uint32_t w[8];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(raw[u][k], false);
-              f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(raw[u][k], true);
-              bf16x2 blo = {(__bf16)lo.x, (__bf16)lo.y};
-              bf16x2 bhi = {(__bf16)hi.x, (__bf16)hi.y};
-              w[2 * k] = __builtin_bit_cast(uint32_t, blo);
-              w[2 * k + 1] = __builtin_bit_cast(uint32_t, bhi);
-            }
-            *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc)) = u32x4{w[0], w[1], w[2], w[3]};
-            *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc + 1)) = u32x4{w[4], w[5], w[6], w[7]};
-          }
+          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc)) = u32x4{w[0], w[1], w[2], w[3]};
+          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc + 1)) = u32x4{w[4], w[5], w[6], w[7]};
         }
         if (tid < kTile) {
-          bool ok = full || retained(pos0 + tid, L, p.S, p.W);
-          float sc = ok ? p.kv_scales[(size_t)page * kPage + slot0 + tid] : 0.f;
-          *LDS_PTR(float, lds_scales + buf * kScaleBytes + tid * 4) = sc;
+          const bool ok = full || retained(pos0 + tid, L, p.S, p.W);
+          const float sc = ok ? p.kv_scales[(size_t)page * kPage + slot0 + tid] : 0.f;
+          *LDS_PTR(float, lds_scales + stage * kScaleBytes + tid * 4) = sc;
         }
       }
     };
+    // Wait for this wave's share of tile `it`; the tile after it may still be in flight.
+    auto wait_tile = [&](int it) {
+      if (it + 1 < n_tiles && tile_is_dma(it + 1)) wait_vm<kDmaPerTile>();
+      else wait_vm<0>();
+    };
 
-    // One pass over the segment's tiles.  MAX_ONLY: only the per-head maximum of the
-    // logits (log2 domain) is formed; otherwise the full softmax-weighted sum.
-    f32x16 acc[kV / 32];
-    float ref = 0.f, l_run = 0.f;
-    bool overflow = false;
+    // The first two tiles start moving before anything else (Q is fetched meanwhile).
+    if (n_tiles > 0) issue_tile(0);
+    if (n_tiles > 1) issue_tile(1);
 
-    auto run_pass = [&](auto max_only_tag, float ref_in) -> float {
-      constexpr bool MAX_ONLY = decltype(max_only_tag)::value;
-      float mx_all = -INFINITY;
-      bool have_ref = !MAX_ONLY && ref_in == ref_in;  // NaN = choose from the first block
-      ref = have_ref ? ref_in : 0.f;
-      l_run = 0.f;
-      overflow = false;
-      if constexpr (!MAX_ONLY) {
+    // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
+    bf16x8 qf[kQK / 16];
+    {
+      // heads past H (a partly filled wave) read the last real head; their results are never written
+      const uint16_t* qrow = p.q + ((size_t)sg.b * p.H + (head_ok ? head : p.H - 1)) * kQK + g * 8;
 #pragma unroll
-        for (int cb = 0; cb < kV / 32; ++cb)
+      for (int ks = 0; ks < kQK / 16; ++ks)
+        qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
+    }
+
+    constexpr int kDepth = 4;           // LDS fragment requests kept in flight
+    constexpr int kNK = kQK / 16;       // 36 MFMAs for S^T
+    constexpr int kNV = 2 * (kV / 32);  // 32 MFMAs for O^T
+
+    // The MFMAs are volatile assembly, which the scheduler does not move loads across,
+    // so the LDS reads are software-pipelined by hand: each fragment is requested kDepth
+    // MFMAs ahead of its use.
+    auto load_k = [&](uint32_t st, int ks) -> bf16x8 {
+      if (ks < 32) return *LDS_PTR(bf16x8, st + (a_main ^ ((ks & 7) << 5)) + (ks >> 3) * 256);
+      return *LDS_PTR(bf16x8, st + (a_tail ^ ((ks - 32) << 5)));
+    };
+    auto load_v = [&](uint32_t st, int j) -> bf16x8 {  // j = th * 16 + cb
+      const int th = j >> 4, cb = j & 15;
+      const uint32_t base = st + th * 16 * kMainRowBytes + (cb >> 2) * 256;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (v_base[0] ^ ((cb & 3) << 6))));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (v_base[1] ^ ((cb & 3) << 6))));
+      return __builtin_bit_cast(bf16x8, s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+    };
+    // S^T of the tile in stage `st`; the first V^T fragments of stage `st_v` are requested
+    // behind the last K fragments.
+    auto qk_tile = [&](uint32_t st, f32x16& s, bf16x8 (&vf)[kDepth], uint32_t st_v) {
+      bf16x8 kf[kDepth];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
+      for (int d = 0; d < kDepth; ++d) kf[d] = load_k(st, d);
+#pragma unroll
+      for (int ks = 0; ks < kNK; ++ks) {
+        if (ks == 0) mfma_s_first(s, kf[ks % kDepth], qf[ks]);
+        else mfma_s(s, kf[ks % kDepth], qf[ks]);
+        if (ks + kDepth < kNK) kf[ks % kDepth] = load_k(st, ks + kDepth);
+        else vf[ks + kDepth - kNK] = load_v(st_v, ks + kDepth - kNK);
       }
-      if (n_tiles > 0) issue_tile(sg.tile_lo, 0);
-#pragma unroll 1
-      for (int it = 0; it < n_tiles; ++it) {
-        const int buf = it & 1;
-        const int ti = sg.tile_lo + it;
-        __builtin_amdgcn_s_waitcnt(0);  // my loads / LDS writes for this tile are done
-        __syncthreads();                // everyone's are; everyone finished reading the other buffer
-        if (it + 1 < n_tiles) issue_tile(ti + 1, buf ^ 1);
+      settle_s(s);
+    };
+    // Per-lane validity bits of a partial tile: bit i = element i is a retained position
+    // (element i is token (i/4)*8 + g*4 + i%4 of the tile).
+    auto valid_bits = [&](int pos0, bool full) -> uint32_t {
+      if (full) return 0xFFFFu;
+      uint32_t m = 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        m |= (uint32_t)retained(pos0 + (i >> 2) * 8 + g * 4 + (i & 3), L, p.S, p.W) << i;
+      return m;
+    };
+    // logit of element i in the log2 domain
+    auto logit = [&](float sv, int i, int stage, uint32_t vbits) -> float {
+      float x = sv * p.scale_log2;
+      if constexpr (FP8)
+        x *= *LDS_PTR(float, lds_scales + stage * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
+      return (vbits >> i) & 1 ? x : -INFINITY;
+    };
+    auto weight = [&](float x, int i, int stage, float r, float& lsum) -> float {
+      float e = __builtin_amdgcn_exp2f(x - r);
+      lsum += e;
+      if constexpr (FP8)
+        e *= *LDS_PTR(float, lds_scales + stage * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
+      return e;
+    };
 
-        const uint32_t tb_base = lds0 + buf * kTileBytes;
-        const int pos0 = tl.logical(ti) * kTile;
-        const bool full = (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L);
-
-        // The MFMAs are volatile assembly, which the scheduler does not move loads
-        // across, so the LDS reads are software-pipelined by hand: each fragment is
-        // requested kDepth MFMAs ahead of its use.
-        auto load_k = [&](int tb, int ks) -> bf16x8 {
-          if (ks < 32)
-            return *LDS_PTR(bf16x8, tb_base + (a_main ^ ((ks & 7) << 5)) + (ks >> 3) * 256 +
-                                        tb * 32 * kMainRowBytes);
-          return *LDS_PTR(bf16x8, tb_base + (a_tail ^ ((ks - 32) << 5)) + tb * 32 * kTailRowBytes);
-        };
-        auto load_v = [&](int tb, int j) -> bf16x8 {  // j = th * 16 + cb
-          const int th = j >> 4, cb = j & 15;
-          const uint32_t base = tb_base + (tb * 32 + th * 16) * kMainRowBytes + (cb >> 2) * 256;
-          s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + v_off[0][cb & 3]));
-          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + v_off[1][cb & 3]));
-          return __builtin_bit_cast(
-              bf16x8, (__attribute__((ext_vector_type(8))) short){lo[0], lo[1], lo[2], lo[3], hi[0],
-                                                                  hi[1], hi[2], hi[3]});
-        };
-        constexpr int kDepth = 6;
-        constexpr int kNK = kQK / 16;  // 36 MFMAs for S^T
-        constexpr int kNV = 2 * (kV / 32);  // 32 MFMAs for O^T
+    float ref = 0.f, l_run = 0.f;
+    float ref_exact = __builtin_nanf("");  // NaN: take the reference from the first tile
+    f32x16 acc[kV / 32];
 
 #pragma unroll 1
-        for (int tb = 0; tb < kTile / 32; ++tb) {
-          bf16x8 kf[kDepth], vf[kDepth];
+    for (int attempt = 0; attempt < 2; ++attempt) {
+      if (attempt > 0) {
+        if (n_tiles > 0) issue_tile(0);
+        if (n_tiles > 1) issue_tile(1);
+      }
 #pragma unroll
-          for (int d = 0; d < kDepth; ++d) kf[d] = load_k(tb, d);
-
-          // ---- S^T = K . Q^T ----
-          f32x16 s;
+      for (int cb = 0; cb < kV / 32; ++cb)
 #pragma unroll
-          for (int ks = 0; ks < kNK; ++ks) {
-            if (ks == 0) mfma_s_first(s, kf[ks % kDepth], qf[ks]);
-            else mfma_s(s, kf[ks % kDepth], qf[ks]);
-            if (ks + kDepth < kNK) kf[ks % kDepth] = load_k(tb, ks + kDepth);
-            else if constexpr (!MAX_ONLY) vf[(ks + kDepth - kNK) % kDepth] = load_v(tb, ks + kDepth - kNK);
-          }
-          settle_s(s);
+        for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
+      float mx_all = -INFINITY;  // running maximum of this lane's logits
 
-          // ---- logits in the log2 domain, per-token scale (fp8), mask ----
-          // element i is token tb*32 + (i/4)*8 + g*4 + i%4 of the tile
-          const uint32_t sc_base = lds_scales + buf * kScaleBytes + (tb * 32 + g * 4) * 4;
-          float mx = -INFINITY;
+      if (n_tiles > 0) {
+        bf16x8 pf[2], vf[kDepth];
+        f32x16 s;
+
+        // ---- tile 0: S^T, reference, weights (no PV to overlap with yet) ----
+        {
+          wait_tile(0);
+          __syncthreads();
+          if (n_tiles > 2) issue_tile(2);
+          qk_tile(lds0, s, vf, lds0);
+          const int pos0 = tile_pos(0);
+          const uint32_t vbits = valid_bits(pos0, tile_full(pos0));
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            float x = s[i] * p.scale_log2;
-            if constexpr (FP8) x *= *LDS_PTR(float, sc_base + ((i >> 2) * 8 + (i & 3)) * 4);
-            if (!full) {
-              const int tok = tb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-              if (!retained(pos0 + tok, L, p.S, p.W)) x = -INFINITY;
-            }
-            s[i] = x;
-            mx = fmaxf(mx, x);
+            s[i] = logit(s[i], i, 0, vbits);
+            mx_all = fmaxf(mx_all, s[i]);
           }
-          if constexpr (MAX_ONLY) {
-            mx_all = fmaxf(mx_all, mx);
-            continue;
+          if (ref_exact == ref_exact) {
+            ref = ref_exact;
+          } else {
+            const float m2 = fmaxf(mx_all, __shfl_xor(mx_all, 32));
+            ref = m2 == -INFINITY ? 0.f : m2;  // -inf only if the data itself holds -inf / NaN logits
           }
-          if (!have_ref) {  // wave-uniform: first block of the pass
-            float m2 = fmaxf(mx, __shfl_xor(mx, 32));
-            // a block may hold no retained token (its tile still does): wait for a finite maximum
-            if (__any(m2 != -INFINITY)) {
-              ref = m2 == -INFINITY ? 0.f : m2;
-              have_ref = true;
-            }
-          }
-          overflow |= __any(mx - ref > kRefSlack) != 0;
-
-          bf16x8 pf[2];
           float lsum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            float e = __builtin_amdgcn_exp2f(s[i] - ref);
-            lsum += e;
-            if constexpr (FP8) e *= *LDS_PTR(float, sc_base + ((i >> 2) * 8 + (i & 3)) * 4);
-            pf[i >> 3][i & 7] = (__bf16)e;
-          }
-          l_run += lsum;
+          for (int i = 0; i < 16; ++i) pf[i >> 3][i & 7] = (__bf16)weight(s[i], i, 0, ref, lsum);
+          l_run = lsum;
+        }
 
-          // ---- O^T += V^T . P^T ----
+        // ---- tiles 1 .. n-1: S^T of tile `it`, then PV of tile it-1 interleaved with the
+        //      softmax arithmetic of tile `it` ----
+#pragma unroll 1
+        for (int it = 1; it < n_tiles; ++it) {
+          const int stage = it & (kStages - 1);
+          const uint32_t st = lds0 + stage * kStageBytes;
+          const uint32_t st_prev = lds0 + ((it - 1) & (kStages - 1)) * kStageBytes;
+          wait_tile(it);
+          __syncthreads();  // tile `it` is visible; every wave is done with the stage tile it+2 goes to
+          if (it + 2 < n_tiles) issue_tile(it + 2);
+          qk_tile(st, s, vf, st_prev);
+          const int pos0 = tile_pos(it);
+          const uint32_t vbits = valid_bits(pos0, tile_full(pos0));
+          bf16x8 pn[2];
+          float lsum = 0.f;
 #pragma unroll
           for (int j = 0; j < kNV; ++j) {
             mfma_o(acc[j & 15], vf[j % kDepth], pf[j >> 4]);
-            if (j + kDepth < kNV) vf[j % kDepth] = load_v(tb, j + kDepth);
+            if (j + kDepth < kNV) vf[j % kDepth] = load_v(st_prev, j + kDepth);
+            if ((j & 1) == 0) {  // one softmax element of tile `it` per two MFMAs of tile it-1
+              const int i = j >> 1;
+              const float x = logit(s[i], i, stage, vbits);
+              mx_all = fmaxf(mx_all, x);
+              pn[i >> 3][i & 7] = (__bf16)weight(x, i, stage, ref, lsum);
+            }
           }
+          l_run += lsum;
+          pf[0] = pn[0];
+          pf[1] = pn[1];
+        }
+
+        // ---- PV of the last tile ----
+        {
+          const uint32_t st_last = lds0 + ((n_tiles - 1) & (kStages - 1)) * kStageBytes;
+          if (n_tiles > 1) {  // its first fragments were not requested by a following S^T
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) vf[d] = load_v(st_last, d);
+          }
+#pragma unroll
+          for (int j = 0; j < kNV; ++j) {
+            mfma_o(acc[j & 15], vf[j % kDepth], pf[j >> 4]);
+            if (j + kDepth < kNV) vf[j % kDepth] = load_v(st_last, j + kDepth);
+          }
+          settle_o(acc);  // the compiler may move the tile between registers right after this
         }
       }
-      __syncthreads();  // all reads of both buffers are done before anyone reuses them
-      return mx_all;
-    };
 
-    run_pass(std::false_type{}, __builtin_nanf(""));
-    // Did any wave see a logit too far above its reference?  Then redo with the exact maximum.
-    if (tid == 0) *LDS_PTR(int, lds_flag) = 0;
-    __syncthreads();
-    if (overflow && lane == 0) *LDS_PTR(int, lds_flag) = 1;
-    __syncthreads();
-    if (*LDS_PTR(int, lds_flag) != 0) {
-      float m = run_pass(std::true_type{}, 0.f);
-      m = fmaxf(m, __shfl_xor(m, 32));
-      run_pass(std::false_type{}, m == -INFINITY ? 0.f : m);
+      // Did any lane of the work group see a logit too far above its reference?
+      if (tid == 0) *LDS_PTR(int, lds_flag) = 0;
+      __syncthreads();  // also: all reads of the stages are done before they are reused
+      if (attempt == 0 && __any(mx_all - ref > kRefSlack) && lane == 0) *LDS_PTR(int, lds_flag) = 1;
+      __syncthreads();
+      if (*LDS_PTR(int, lds_flag) == 0) break;
+      const float m2 = fmaxf(mx_all, __shfl_xor(mx_all, 32));
+      ref_exact = m2 == -INFINITY ? 0.f : m2;
     }
 
-    // ---- epilogue ----
-#pragma unroll
-    for (int cb = 0; cb < kV / 32; ++cb) settle_o(acc[cb]);
+    // ---- epilogue: normalise, transpose through LDS, write whole rows ----
     l_run += __shfl_xor(l_run, 32);
     const float inv = n_tiles > 0 ? 1.0f / l_run : 0.f;
     const float lse = n_tiles > 0 ? (ref + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : -INFINITY;
-    if (head_ok) {
-      if (sg.slot < 0) {
-        if (g == 0) p.lse[(size_t)sg.b * p.H + head] = lse;
-        if (p.out_fp32) {
-          float* o = (float*)p.out + ((size_t)sg.b * p.H + head) * kV;
+    const bool final_out = sg.slot < 0;
+    const uint32_t ost = lds0 + wave * kOutWaveBytes;  // this wave's staging rows
+    const int heads_here = p.H - h0 < kHeadsPerWave ? p.H - h0 : kHeadsPerWave;  // may be <= 0
+    if (head_ok && g == 0) {
+      if (final_out) p.lse[(size_t)sg.b * p.H + head] = lse;
+      else p.part_lse[(size_t)sg.slot * p.head_block + wave * kHeadsPerWave + n32] = lse;
+    }
+    if (final_out && !p.out_fp32) {
+      // bf16: one round, a staged row is the head's 512 outputs (1024 bytes)
 #pragma unroll
-          for (int cb = 0; cb < kV / 32; ++cb)
+      for (int cb = 0; cb < kV / 32; ++cb)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-              f32x4 v = {acc[cb][i4 * 4] * inv, acc[cb][i4 * 4 + 1] * inv, acc[cb][i4 * 4 + 2] * inv,
-                         acc[cb][i4 * 4 + 3] * inv};
-              *(f32x4*)(o + cb * 32 + i4 * 8 + g * 4) = v;
-            }
-        } else {
-          uint16_t* o = (uint16_t*)p.out + ((size_t)sg.b * p.H + head) * kV;
-#pragma unroll
-          for (int cb = 0; cb < kV / 32; ++cb)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-              bf16x4 v = {(__bf16)(acc[cb][i4 * 4] * inv), (__bf16)(acc[cb][i4 * 4 + 1] * inv),
-                          (__bf16)(acc[cb][i4 * 4 + 2] * inv), (__bf16)(acc[cb][i4 * 4 + 3] * inv)};
-              *(bf16x4*)(o + cb * 32 + i4 * 8 + g * 4) = v;
-            }
+        for (int i4 = 0; i4 < 4; ++i4) {
+          bf16x4 v = {(__bf16)(acc[cb][i4 * 4] * inv), (__bf16)(acc[cb][i4 * 4 + 1] * inv),
+                      (__bf16)(acc[cb][i4 * 4 + 2] * inv), (__bf16)(acc[cb][i4 * 4 + 3] * inv)};
+          *LDS_PTR(bf16x4, ost + n32 * kOutRowBytes + (cb * 32 + i4 * 8 + g * 4) * 2) = v;
         }
-      } else {
-        const int hl = wave * kHeadsPerWave + n32;  // head within the block
-        if (g == 0) p.part_lse[(size_t)sg.slot * p.head_block + hl] = lse;
-        float* o = p.part_o + ((size_t)sg.slot * p.head_block + hl) * kV;
+      uint8_t* dst = (uint8_t*)p.out + ((size_t)sg.b * p.H + h0) * (kV * 2) + lane * 16;
+#pragma unroll 4
+      for (int h = 0; h < heads_here; ++h)
+        *(u32x4*)(dst + (size_t)h * (kV * 2)) = *LDS_PTR(u32x4, ost + h * kOutRowBytes + lane * 16);
+    } else {
+      // fp32 rows (partials or fp32 output): two rounds of 256 columns
+      uint8_t* dst = final_out
+                         ? (uint8_t*)p.out + ((size_t)sg.b * p.H + h0) * (kV * 4)
+                         : (uint8_t*)p.part_o +
+                               ((size_t)sg.slot * p.head_block + wave * kHeadsPerWave) * (kV * 4);
+      dst += lane * 16;
 #pragma unroll
-        for (int cb = 0; cb < kV / 32; ++cb)
+      for (int r = 0; r < 2; ++r) {
+#pragma unroll
+        for (int cb8 = 0; cb8 < 8; ++cb8)
 #pragma unroll
           for (int i4 = 0; i4 < 4; ++i4) {
+            const int cb = r * 8 + cb8;
             f32x4 v = {acc[cb][i4 * 4] * inv, acc[cb][i4 * 4 + 1] * inv, acc[cb][i4 * 4 + 2] * inv,
                        acc[cb][i4 * 4 + 3] * inv};
-            *(f32x4*)(o + cb * 32 + i4 * 8 + g * 4) = v;
+            *LDS_PTR(f32x4, ost + n32 * kOutRowBytes + (cb8 * 32 + i4 * 8 + g * 4) * 4) = v;
           }
+#pragma unroll 4
+        for (int h = 0; h < heads_here; ++h)
+          *(u32x4*)(dst + (size_t)h * (kV * 4) + r * 1024) =
+              *LDS_PTR(u32x4, ost + h * kOutRowBytes + lane * 16);
       }
     }
+    __syncthreads();  // staging rows are free again before the next segment's tiles arrive
   }
 }
 

@@ -22,7 +22,7 @@
 
 namespace omniattn {
 
-constexpr int kTile = 64;    // KV tokens per tile (divides the 128-token page)
+constexpr int kTile = 32;    // KV tokens per tile (divides the 128-token page)
 constexpr int kQK = OMNIATTN_QK_DIM;
 constexpr int kV = OMNIATTN_V_DIM;
 constexpr int kPage = OMNIATTN_PAGE;
