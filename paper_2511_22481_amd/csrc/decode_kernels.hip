@@ -388,7 +388,11 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             ref = ref_exact;
           } else {
             const float m2 = fmaxf(mx_all, __shfl_xor(mx_all, 32));
-            ref = m2 == -INFINITY ? 0.f : m2;  // -inf only if the data itself holds -inf / NaN logits
+            // An integer reference makes weights computed against different references
+            // differ by exact powers of two, so their bf16 roundings agree between
+            // different partitions of the same sequence.  (-inf only if the data itself
+            // holds -inf / NaN logits.)
+            ref = m2 == -INFINITY ? 0.f : ceilf(m2);
           }
           float lsum = 0.f;
 #pragma unroll
@@ -450,7 +454,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       __syncthreads();
       if (*LDS_PTR(int, lds_flag) == 0) break;
       const float m2 = fmaxf(mx_all, __shfl_xor(mx_all, 32));
-      ref_exact = m2 == -INFINITY ? 0.f : m2;
+      ref_exact = m2 == -INFINITY ? 0.f : ceilf(m2);
     }
 
     // ---- epilogue: normalise, transpose through LDS, write whole rows ----

@@ -64,13 +64,17 @@ def errors(out_gpu, lse_gpu, out_ref, lse_ref):
 def assert_parity(inp, out_gpu, lse_gpu, pairs=None, rel_l2=None, row_rel_l2=None, what=""):
     out_ref, lse_ref = run_oracle(inp, pairs=pairs)
     if pairs is not None:
-        idx = torch.as_tensor(np.asarray(pairs), dtype=torch.long)
+        idx = torch.as_tensor(np.asarray(pairs), dtype=torch.long, device=out_gpu.device)
         out_gpu = out_gpu[idx[:, 0], idx[:, 1]]
         lse_gpu = lse_gpu[idx[:, 0], idx[:, 1]]
     e = errors(out_gpu, lse_gpu, out_ref, lse_ref)
     tol = REL_L2[inp.kv_dtype] if rel_l2 is None else rel_l2
     msg = f"{what} {e}"
-    assert e["max_abs"] <= MAX_ABS, msg
+    # The absolute bound is stated for the workloads' value scale (|out| well below 1).  Test
+    # inputs with larger values scale it by the largest reference magnitude: rounding the
+    # output to bf16 alone costs 2^-9 of that.
+    scale = max(1.0, float(np.nanmax(np.abs(out_ref))) if out_ref.size else 1.0)
+    assert e["max_abs"] <= MAX_ABS * scale, msg
     assert e["rel_l2"] <= tol, msg
     assert e["lse_abs"] <= LSE_ABS, msg
     if row_rel_l2 is not None:

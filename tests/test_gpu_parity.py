@@ -1,0 +1,241 @@
+"""GPU parity: the HIP decode path against the fp64 CPU oracle, element by element,
+through the C ABI (paper section 3.2.1: softmax attention over the sink + recent set).
+
+Tolerances (see parity.py): max-abs 2e-2, rel-L2 1e-2 (bf16 cache) / 5e-2 (fp8 cache),
+lse 1e-3.  With the workloads' near-uniform softmax the max-abs bound can hardly
+fail, so most cases use larger logits ("stress") and per-row rel-L2 as the live checks.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_22481_amd as oa
+import parity
+from workloads import get_config, make_custom, make_inputs, poison_unretained
+
+pytestmark = pytest.mark.gpu
+
+PAGE = 128
+
+
+def keep_lists(lens, S, W):
+    out = []
+    for L in lens:
+        n = ((L + PAGE - 1) // PAGE) * PAGE
+        out.append([(j < L) and (j < S or j >= L - W) for j in range(n)])
+    return out
+
+
+def sample_pairs(B, H, n, seed):
+    rng = np.random.default_rng(seed)
+    pairs = {(int(rng.integers(B)), int(rng.integers(H))) for _ in range(n)}
+    pairs |= {(0, 0), (B - 1, H - 1), (0, H - 1), (B - 1, 0)}
+    return sorted(pairs)
+
+
+# ------------------------------------------------------------------ small, full compare ---
+def test_tiny_config_all_elements():
+    inp = make_inputs(get_config("tiny"), device="cuda")
+    out, lse, plan = parity.run_gpu(inp)
+    e = parity.assert_parity(inp, out, lse, row_rel_l2=1e-2, what="tiny")
+    assert plan.retained_tokens == 4 * (64 + 512)
+    assert e["rel_l2"] < 5e-3
+
+
+@pytest.mark.parametrize("H", [16, 48, 128, 160])
+@pytest.mark.parametrize("q_std", [1.0 / 24, 2.0])
+def test_ragged_unaligned(H, q_std):
+    """Several tiles, ragged tails, unaligned S / W / L, shuffled pages with spare pages."""
+    lens = [700, 64, 2500, 1, 129, 33]
+    inp = parity.to_device(make_custom(len(lens), H, lens, 100, 300, seed=3 + H, q_std=q_std,
+                                       kv_std=0.5, spare_pages=3))
+    out, lse, _ = parity.run_gpu(inp)
+    parity.assert_parity(inp, out, lse, row_rel_l2=1e-2, what=f"ragged H={H}")
+
+
+@pytest.mark.parametrize("S,W", [(0, 200), (37, 0), (0, 0), (5000, 0), (0, 5000), (64, 64),
+                                 (31, 33), (128, 2048), (1, 1)])
+def test_sink_window_edge_values(S, W):
+    lens = [0, 1, 31, 32, 33, 64, 500, 3000]
+    inp = parity.to_device(make_custom(len(lens), 32, lens, S, W, seed=S * 7 + W, q_std=1.5, kv_std=1.0))
+    out, lse, _ = parity.run_gpu(inp)
+    parity.assert_parity(inp, out, lse, row_rel_l2=1e-2, what=f"S={S} W={W}")
+    if S == 0 and W == 0:
+        assert torch.all(out == 0) and torch.all(torch.isneginf(lse))
+
+
+@pytest.mark.parametrize("c", [1.0, 4.0])
+def test_stress_logits(c):
+    """Logits ~ N(0, c^2) in natural units: exercises the scale, the reference and exp range."""
+    q_std = c * np.sqrt(192.0)       # q.k/sqrt(192) then has standard deviation c for k_std = 1/24
+    inp = parity.to_device(make_custom(3, 128, [2176, 900, 4000], 128, 2048, seed=11, q_std=q_std,
+                                       kv_std=1.0 / 24))
+    out, lse, _ = parity.run_gpu(inp)
+    ro, rl = parity.run_oracle(inp)
+    assert float(np.std(rl)) > 0.0
+    e = parity.errors(out, lse, ro, rl)
+    assert e["rel_l2"] <= 1e-2 and e["worst_row_rel_l2"] <= 2e-2 and e["lse_abs"] <= 1e-3, e
+
+
+def test_fp32_output():
+    inp = parity.to_device(make_custom(2, 64, [1000, 300], 64, 256, seed=5, q_std=1.0, kv_std=1.0))
+    out, lse, _ = parity.run_gpu(inp, out_dtype=torch.float32)
+    assert out.dtype == torch.float32
+    e = parity.assert_parity(inp, out, lse, row_rel_l2=8e-3)
+    out16, _, _ = parity.run_gpu(inp)
+    assert torch.equal(out.to(torch.bfloat16), out16)   # same arithmetic, only the rounding differs
+
+
+# ---------------------------------------------------------------------------- invariants ---
+def test_poisoned_unretained_slots_have_no_influence():
+    lens = [1000, 77, 400, 2600]
+    S, W = 40, 150
+    for kv_dtype in ("bf16", "fp8"):
+        inp = parity.to_device(make_custom(4, 128, lens, S, W, seed=8, kv_dtype=kv_dtype, q_std=1.0,
+                                           kv_std=1.0, spare_pages=4))
+        out0, lse0, plan = parity.run_gpu(inp)
+        poison_unretained(inp, keep_lists(lens, S, W))
+        assert torch.isnan(inp.kv_cache.float()).any()
+        out1, lse1, _ = parity.run_gpu(inp, plan=plan)
+        assert not torch.isnan(out1.float()).any() and not torch.isnan(lse1).any()
+        assert torch.equal(out0, out1) and torch.equal(lse0, lse1)
+        parity.assert_parity(inp, out1, lse1, row_rel_l2=1e-2, what=f"poison {kv_dtype}")
+        # unread page-table entries may be garbage
+        tab = inp.page_table.clone()
+        for b, L in enumerate(lens):
+            for pg in range(tab.shape[1]):
+                lo, hi = pg * PAGE, (pg + 1) * PAGE
+                if not any(j < S or j >= L - W for j in range(lo, min(hi, L))):
+                    tab[b, pg] = -12345
+        inp.page_table = tab
+        out2, lse2, _ = parity.run_gpu(inp, plan=plan)
+        assert torch.equal(out0, out2) and torch.equal(lse0, lse2)
+
+
+def test_retained_nan_propagates():
+    inp = parity.to_device(make_custom(2, 32, [300, 300], 10, 20, seed=2, q_std=1.0, kv_std=1.0))
+    page = int(inp.page_table[0, 0])
+    inp.kv_cache[page, 3, 100] = float("nan")            # position 3 is a sink of sequence 0
+    out, lse, _ = parity.run_gpu(inp)
+    assert torch.isnan(out[0].float()).all() and not torch.isnan(out[1].float()).any()
+
+
+def test_boundary_spikes():
+    """One huge-logit token next to each edge of the retained set counts iff the rule says so."""
+    L, S, W = 1000, 130, 260
+    scale = float(np.float32(192.0 ** -0.5))
+    for j, counted in {0: True, S - 1: True, S: False, L - W - 1: False, L - W: True,
+                       L - 1: True}.items():
+        inp = make_custom(1, 16, [L], S, W, seed=17, q_std=1.0 / 24, kv_std=1.0 / 24)
+        inp.q.zero_()
+        inp.q[0, :, 530] = 64.0
+        row = torch.zeros(576)
+        row[530] = 16.0
+        row[7] = 3.0
+        inp.kv_cache[int(inp.page_table[0, j // PAGE]), j % PAGE] = row.to(torch.bfloat16)
+        inp = parity.to_device(inp)
+        out, lse, _ = parity.run_gpu(inp)
+        parity.assert_parity(inp, out, lse, what=f"spike at {j}")
+        if counted:
+            assert abs(float(out[0, 0, 7]) - 3.0) < 0.02 and abs(float(lse[0, 0]) - 1024 * scale) < 1e-3
+        else:
+            assert abs(float(out[0, 0, 7])) < 0.1 and float(lse[0, 0]) < 10.0
+
+
+def test_page_permutation_is_bitwise_invariant():
+    lens = [640, 130, 1025]
+    a = make_custom(3, 128, lens, 100, 260, seed=21, q_std=1.0, kv_std=1.0, spare_pages=3)
+    g = torch.Generator().manual_seed(99)
+    perm = torch.randperm(a.num_pages, generator=g)
+    b = make_custom(3, 128, lens, 100, 260, seed=21, q_std=1.0, kv_std=1.0, spare_pages=3)
+    b.kv_cache[perm] = a.kv_cache.clone()
+    tab = a.page_table.clone()
+    valid = tab >= 0
+    tab[valid] = perm[tab[valid].long()].to(torch.int32)
+    b.page_table = tab
+    oa_, la, _ = parity.run_gpu(parity.to_device(a))
+    ob, lb, _ = parity.run_gpu(parity.to_device(b))
+    assert torch.equal(oa_, ob) and torch.equal(la, lb)
+
+
+def test_split_count_invariance_and_determinism():
+    inp = parity.to_device(make_custom(3, 128, [3000, 700, 97], 128, 2048, seed=9, q_std=1.5, kv_std=1.0))
+    ref_out, ref_lse = parity.run_oracle(inp)
+    base = None
+    for hint in (1, 2, 3, 7, 1000, 0):
+        out, lse, plan = parity.run_gpu(inp, out_dtype=torch.float32, num_splits_hint=hint)
+        e = parity.errors(out, lse, ref_out, ref_lse)
+        assert e["rel_l2"] <= 1e-2 and e["lse_abs"] <= 1e-3, (hint, e)
+        if base is None:
+            base = out
+        else:   # different partitions only reassociate fp32 sums (and round P per tile identically)
+            rel = float(torch.linalg.norm(out - base) / torch.linalg.norm(base))
+            assert rel <= 5e-5, (hint, rel)
+        out2, lse2, _ = parity.run_gpu(inp, out_dtype=torch.float32, plan=plan)
+        assert torch.equal(out, out2) and torch.equal(lse, lse2), "same plan must be bitwise repeatable"
+
+
+def test_reference_overflow_retry():
+    """Logits that climb far above the first tile's maximum force the second attempt."""
+    L = 640
+    inp = make_custom(2, 32, [L, L], 0, 4096, seed=4, q_std=1.0 / 24, kv_std=1.0 / 24)
+    inp.q.zero_()
+    inp.q[:, :, 540] = 64.0
+    for b in range(2):
+        for j in range(L):
+            # the logit grows to ~131 in log2 units along the sequence, the first tile stays below 6
+            v = torch.zeros(576)
+            v[540] = float(np.float32(j // 8)) / 4.0
+            v[3] = float(j % 5)
+            inp.kv_cache[int(inp.page_table[b, j // PAGE]), j % PAGE] = v.to(torch.bfloat16)
+    inp = parity.to_device(inp)
+    out, lse, _ = parity.run_gpu(inp, out_dtype=torch.float32)
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+    parity.assert_parity(inp, out, lse, row_rel_l2=1e-2, what="overflow retry")
+
+
+def test_workspace_and_argument_errors():
+    inp = parity.to_device(make_custom(1, 128, [32 * 40], 0, 4096, seed=1))
+    plan = oa.omniattn_plan(inp.seq_lens_host, batch=1, num_heads=128, max_pages_per_seq=inp.max_pages,
+                            num_pages=inp.num_pages, sink=0, window=4096, softmax_scale=0.1,
+                            num_splits_hint=4)
+    assert plan.workspace_bytes > 0
+    out = torch.empty((1, 128, 512), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((1, 128), dtype=torch.float32, device="cuda")
+    with pytest.raises(oa.OmniAttnError) as e:
+        oa.omniattn_decode(plan, inp.q, inp.kv_cache, None, inp.page_table, out, lse, None)
+    assert e.value.code == -3
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(oa.OmniAttnError) as e:
+        oa.omniattn_decode(plan, inp.q, inp.kv_cache, None, inp.page_table, out, lse, small)
+    assert e.value.code == -3
+
+
+# ------------------------------------------------------------------------------- fp8 ---
+@pytest.mark.parametrize("q_std", [1.0 / 24, 0.5])
+def test_fp8_cache(q_std):
+    lens = [900, 300, 2176, 65]
+    inp = parity.to_device(make_custom(4, 128, lens, 64, 256, seed=5, kv_dtype="fp8", q_std=q_std, kv_std=1.0))
+    out, lse, _ = parity.run_gpu(inp)
+    parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what="fp8")
+
+
+# --------------------------------------------------- full-size workloads, sampled outputs ---
+@pytest.mark.parametrize("name,n_pairs", [("r1_b64_32k", 64), ("dense_b32_4k", 48), ("fp8_b32_128k", 32),
+                                          ("mixed_b256", 64)])
+def test_full_size_workload_sampled(name, n_pairs):
+    """The launch configuration bench.py times; outputs sampled per (sequence, head)."""
+    cfg = get_config(name)
+    inp = make_inputs(cfg, device="cuda")
+    out, lse, plan = parity.run_gpu(inp)
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    out2, lse2, _ = parity.run_gpu(inp, plan=plan)
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+    pairs = sample_pairs(inp.batch, inp.heads, n_pairs, seed=cfg.seed)
+    e = parity.assert_parity(inp, out, lse, pairs=pairs, row_rel_l2=2e-2, what=name)
+    if name == "dense_b32_4k":            # S + W >= L: equals full attention, every token counted once
+        assert plan.retained_tokens == cfg.batch * cfg.ctx
+    # the stress variant of the same shape: logits of order one
+    inp.q = (inp.q.float() * (24.0 * np.sqrt(192.0) * (1.0 if cfg.kv_dtype == "bf16" else 1 / 24))).to(torch.bfloat16)
+    out, lse, _ = parity.run_gpu(inp, plan=plan)
+    parity.assert_parity(inp, out, lse, pairs=pairs, row_rel_l2=2e-2, what=name + " stress")
