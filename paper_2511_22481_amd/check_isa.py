@@ -34,6 +34,21 @@ def _regs(text):
 def check(asm_text, kernel_filter="decode_kernel"):
     """Returns a list of violation strings (empty = fine)."""
     problems = []
+    # 1. no register spill traffic inside a basic block that runs a whole MFMA chain: a
+    #    spill reload waits on the vector-memory counter and would drain the tile prefetch
+    block, name, in_k = [], None, False
+    for raw in asm_text.splitlines() + ["end:"]:
+        line = raw.split(";")[0].strip()
+        if line.endswith(":"):
+            if in_k and sum(l.startswith("v_mfma") for l in block) >= 60 and any(
+                    l.startswith("scratch_") for l in block):
+                problems.append(f"register spill traffic inside the MFMA loop of block {name}")
+            if not line.startswith("."):
+                in_k = kernel_filter in line
+            block, name = [], line
+        elif line:
+            block.append(line)
+    # 2. MFMA results read too early
     in_kernel = False
     pending = {}  # register -> wait states elapsed since the MFMA that writes it
     for lineno, raw in enumerate(asm_text.splitlines(), 1):
@@ -64,10 +79,21 @@ def check(asm_text, kernel_filter="decode_kernel"):
             states = int(rest.strip()) + 1
         else:
             need = MEM_STATES if op.startswith(_MEM_PREFIXES) else VALU_STATES
-            for r in _regs(rest):
+            operands = rest.split(",")
+            writes_first = (op.startswith("v_") and not op.startswith("v_cmp")) or "_load" in op or \
+                op.startswith("ds_read") or op.startswith("ds_bpermute")
+            read_text = ",".join(operands[1:]) if writes_first else rest
+            for r in _regs(read_text):
                 if r in pending and pending[r] < need:
                     problems.append(f"line {lineno}: {pending[r]} wait states after MFMA write of "
                                     f"{r[0]}{r[1]}: {line}")
+            if writes_first:  # overwritten: later uses no longer see the MFMA's result
+                for r in _regs(operands[0]):
+                    if r in pending:
+                        if pending[r] < VALU_STATES:
+                            problems.append(f"line {lineno}: overwrite {pending[r]} wait states after MFMA "
+                                            f"write of {r[0]}{r[1]}: {line}")
+                        del pending[r]
         for r in list(pending):
             pending[r] += states
             if pending[r] >= 64:

@@ -59,7 +59,9 @@ constexpr int kTailBase = kTile * kMainRowBytes;                      // 32,768
 constexpr int kStageBytes = kTile * (kMainRowBytes + kTailRowBytes);  // 36,864
 constexpr int kStages = 4;
 constexpr int kScaleBytes = kTile * 4;  // per-token fp32 scales of one stage (fp8 cache)
-constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16;  // + retry flag
+constexpr int kPageIdBytes = kMaxSegTiles * 4;  // physical page of every tile of the segment
+constexpr int kJunkBytes = 1024;  // target of the direct loads issued for tiles that do not exist
+constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16 + kPageIdBytes + kJunkBytes;  // 16: retry flag
 __host__ __device__ constexpr int swz_main(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 __host__ __device__ constexpr int swz_tail(int r) { return (r >> 1) & 7; }
 // byte offset of chunk c (0..71) of row r inside a stage
@@ -116,15 +118,18 @@ __device__ __forceinline__ void dma16(const uint8_t* base, uint32_t off, uint32_
   const uint32_t b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
   const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
   const uint32_t slds = __builtin_amdgcn_readfirstlane(lds_base);
-  uint32_t saved_m0;
+  // M0 carries the LDS base.  Nothing else in these kernels uses M0 (no indirect register
+  // addressing, no GWS, no compiler-issued LDS-DMA), so it is simply overwritten.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
   asm volatile(
-      "s_mov_b32 %0, m0\n\t"
-      "s_mov_b32 m0, %3\n\t"
+      "s_mov_b32 m0, %2\n\t"
       "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2\n\t"
-      "s_mov_b32 m0, %0"
-      : "=&s"(saved_m0)
-      : "v"(off), "s"(sbase), "s"(slds));
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(off), "s"(sbase), "s"(slds)
+      : "m0");
+#pragma clang diagnostic pop
 }
 // Wait until at most N of this wave's vector-memory operations are outstanding.
 template <int N>
@@ -148,6 +153,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds_raw;  // LDS byte address of stage 0
   const uint32_t lds_scales = lds0 + kStages * kStageBytes;
   const uint32_t lds_flag = lds_scales + kStages * kScaleBytes;
+  const uint32_t lds_pages = lds_flag + 16;
+  const uint32_t lds_junk = lds_pages + kPageIdBytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -194,14 +201,25 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     auto tile_full = [&](int pos0) {
       return (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L);
     };
-    // Is tile `it` of this segment fetched by direct loads (whole tile retained, bf16)?
-    auto tile_is_dma = [&](int it) { return !FP8 && tile_full(tile_pos(it)); };
-
     // ---- tile loader: wave w fills rows [w * kRowsPerWave, ...) of stage it & 3 ----
-    auto issue_tile = [&](int it) {
+    // A tile is fetched by kDmaPerTile direct-load instructions per wave.  Exactly that
+    // many are issued for every tile index, also for tiles past the segment's end and for
+    // tiles filled through registers (partial tiles, fp8): those point at a junk region.
+    // The count of loads in flight per tile is therefore a constant, which is what the
+    // vmcnt-based wait_tile relies on, and the loop needs no branch per load.
+    struct TileSrc {
+      const uint8_t* gbase;   // first byte of the tile's rows in the cache (or any valid address)
+      uint32_t lmain, ltail;  // LDS destinations of row 0 (main part, tail part)
+      uint32_t mstride, tstride;  // 1024 / 128, or 0 for the junk target
+    };
+    auto prep_tile = [&](int it) -> TileSrc {
+      TileSrc ts;
+      ts.gbase = (const uint8_t*)p.q;
+      ts.lmain = ts.ltail = lds_junk;
+      ts.mstride = ts.tstride = 0;
+      if (it >= n_tiles) return ts;
       const int pos0 = tile_pos(it);
-      const int page = __builtin_amdgcn_readfirstlane(
-          p.page_table[(size_t)sg.b * p.max_pages + (pos0 >> 7)]);
+      const int page = __builtin_amdgcn_readfirstlane(*LDS_PTR(int, lds_pages + it * 4));
       const int slot0 = pos0 & (kPage - 1);
       const bool full = tile_full(pos0);
       const int stage = it & (kStages - 1);
@@ -210,25 +228,11 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       if constexpr (!FP8) {
         const uint8_t* gbase = p.kv + ((size_t)page * kPage + slot0) * kRowBytes;
         if (full) {
-          // The per-lane offsets below are loop invariant; recomputing them (an XOR and a
-          // shift) is cheaper than keeping them alive across the MFMA loops, so the lane id
-          // is passed through an opaque move that stops the compiler hoisting them.
-          uint32_t l = lane;
-          asm volatile("" : "+v"(l));
-          // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
-#pragma unroll
-          for (int j = 0; j < kRowsPerWave; ++j) {
-            const int row = row_w0 + j;
-            const uint32_t off = row * kRowBytes + ((l ^ swz_main(row)) << 4);
-            dma16(gbase, off, lbase + row * kMainRowBytes);
-          }
-          // tail part: one instruction per 8 rows; lane l fetches row l / 8, rope chunk (l & 7) ^ swz
-#pragma unroll
-          for (int k = 0; k < kRowsPerWave / 8; ++k) {
-            const uint32_t row = row_w0 + 8 * k + (l >> 3);
-            const uint32_t off = row * kRowBytes + ((64 + ((l & 7) ^ swz_tail(row))) << 4);
-            dma16(gbase, off, lbase + kTailBase + (row_w0 + 8 * k) * kTailRowBytes);
-          }
+          ts.gbase = gbase;
+          ts.lmain = lbase;
+          ts.ltail = lbase + kTailBase;
+          ts.mstride = kMainRowBytes;
+          ts.tstride = kTailRowBytes;
         } else {
           // partial tile: rows outside the retained set are zero-filled, never loaded
           // (their contents are unspecified and 0 * NaN would poison the PV product)
@@ -243,8 +247,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           }
         }
       } else {
-        // fp8 rows: 36 chunks of 16 codes; widen each code exactly to bf16, keep the
-        // per-token scale aside (it multiplies the logit and the softmax weight).
+        // fp8 rows: 36 chunks of 16 codes; every code is widened exactly to bf16 and the
+        // token's fp32 scale is kept aside: it multiplies the logit (after QK^T) and the
+        // softmax weight (before PV), both in fp32, so dequantisation adds no rounding.
         const uint8_t* gbase = p.kv + ((size_t)page * kPage + slot0) * kQK;
         constexpr int n_chunks = kTile * (kQK / 16);  // 1152
 #pragma unroll 1
@@ -272,18 +277,35 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           *LDS_PTR(float, lds_scales + stage * kScaleBytes + tid * 4) = sc;
         }
       }
+      return ts;
     };
-    // Wait for this wave's share of tile `it`; the tile after it may still be in flight.
-    auto wait_tile = [&](int it) {
-      if (it + 1 < n_tiles && tile_is_dma(it + 1)) wait_vm<kDmaPerTile>();
-      else wait_vm<0>();
+    // Direct load number k (0 .. kDmaPerTile-1) of a prepared tile.  The per-lane offsets
+    // are recomputed each time (an XOR and a shift) from a lane id that went through an
+    // opaque move: kept alive across the MFMA loop they would cost registers it lacks.
+    auto dma_piece = [&](const TileSrc& ts, int k) {
+      uint32_t l = lane;
+      asm volatile("" : "+v"(l));
+      const int row_w0 = wave * kRowsPerWave;
+      if (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
+        const int row = row_w0 + k;
+        dma16(ts.gbase, row * kRowBytes + ((l ^ swz_main(row)) << 4), ts.lmain + row * ts.mstride);
+      } else {  // tail part: one instruction per 8 rows; lane l fetches row l / 8, rope chunk (l & 7) ^ swz
+        const int r8 = row_w0 + 8 * (k - kRowsPerWave);
+        const uint32_t row = r8 + (l >> 3);
+        dma16(ts.gbase, row * kRowBytes + ((64 + ((l & 7) ^ swz_tail(row))) << 4), ts.ltail + r8 * ts.tstride);
+      }
     };
-
-    // The first two tiles start moving before anything else (Q is fetched meanwhile).
-    if (n_tiles > 0) issue_tile(0);
-    if (n_tiles > 1) issue_tile(1);
+    auto issue_tile = [&](int it) {
+      const TileSrc ts = prep_tile(it);
+#pragma unroll
+      for (int k = 0; k < kDmaPerTile; ++k) dma_piece(ts, k);
+    };
+    // Wait for this wave's share of a tile: only the loads of the tile after it may still
+    // be in flight.
+    auto wait_tile = [&]() { wait_vm<kDmaPerTile>(); };
 
     // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
+    // Requested first; the page ids below and the first tiles travel at the same time.
     bf16x8 qf[kQK / 16];
     {
       // heads past H (a partly filled wave) read the last real head; their results are never written
@@ -292,63 +314,69 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       for (int ks = 0; ks < kQK / 16; ++ks)
         qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
     }
+    // Physical page of every tile of the segment, gathered once into LDS: the loop then
+    // needs no global load of its own besides the direct tile loads (whose completion
+    // counter must not be disturbed by other vector-memory waits).
+    for (int t = tid; t < n_tiles; t += WAVES * 64)
+      *LDS_PTR(int, lds_pages + t * 4) = p.page_table[(size_t)sg.b * p.max_pages + (tile_pos(t) >> 7)];
+    __syncthreads();
+    issue_tile(0);
+    issue_tile(1);
 
-    constexpr int kDepth = 4;           // LDS fragment requests kept in flight
+    constexpr int kRing = 8;            // LDS fragment requests kept in flight
     constexpr int kNK = kQK / 16;       // 36 MFMAs for S^T
     constexpr int kNV = 2 * (kV / 32);  // 32 MFMAs for O^T
 
-    // The MFMAs are volatile assembly, which the scheduler does not move loads across,
-    // so the LDS reads are software-pipelined by hand: each fragment is requested kDepth
-    // MFMAs ahead of its use.
+    // The MFMAs are volatile assembly, which the scheduler does not move loads across, so
+    // the LDS reads are software-pipelined by hand through one ring of kRing fragments:
+    // the MFMAs of an iteration (36 for S^T of tile `it`, then 32 for PV of tile it-1)
+    // consume the ring in order and each fragment is requested kRing MFMAs ahead.
+    // The XORed per-lane offsets are recomputed at every use (one vector-ALU op): kept as
+    // loop invariants they would cost eight more registers than the loop can spare, and a
+    // spilled register's reload waits on the vector-memory counter, which would drain the
+    // tile prefetch.  The bases pass through an opaque move once per tile for that reason.
+    uint32_t am = a_main, at = a_tail, vb0 = v_base[0], vb1 = v_base[1];
+    auto launder_offsets = [&]() { asm volatile("" : "+v"(am), "+v"(at), "+v"(vb0), "+v"(vb1)); };
     auto load_k = [&](uint32_t st, int ks) -> bf16x8 {
-      if (ks < 32) return *LDS_PTR(bf16x8, st + (a_main ^ ((ks & 7) << 5)) + (ks >> 3) * 256);
-      return *LDS_PTR(bf16x8, st + (a_tail ^ ((ks - 32) << 5)));
+      if (ks < 32) return *LDS_PTR(bf16x8, st + (am ^ ((ks & 7) << 5)) + (ks >> 3) * 256);
+      return *LDS_PTR(bf16x8, st + (at ^ ((ks - 32) << 5)));
     };
     auto load_v = [&](uint32_t st, int j) -> bf16x8 {  // j = th * 16 + cb
       const int th = j >> 4, cb = j & 15;
       const uint32_t base = st + th * 16 * kMainRowBytes + (cb >> 2) * 256;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (v_base[0] ^ ((cb & 3) << 6))));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (v_base[1] ^ ((cb & 3) << 6))));
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (vb0 ^ ((cb & 3) << 6))));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (vb1 ^ ((cb & 3) << 6))));
       return __builtin_bit_cast(bf16x8, s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
-    };
-    // S^T of the tile in stage `st`; the first V^T fragments of stage `st_v` are requested
-    // behind the last K fragments.
-    auto qk_tile = [&](uint32_t st, f32x16& s, bf16x8 (&vf)[kDepth], uint32_t st_v) {
-      bf16x8 kf[kDepth];
-#pragma unroll
-      for (int d = 0; d < kDepth; ++d) kf[d] = load_k(st, d);
-#pragma unroll
-      for (int ks = 0; ks < kNK; ++ks) {
-        if (ks == 0) mfma_s_first(s, kf[ks % kDepth], qf[ks]);
-        else mfma_s(s, kf[ks % kDepth], qf[ks]);
-        if (ks + kDepth < kNK) kf[ks % kDepth] = load_k(st, ks + kDepth);
-        else vf[ks + kDepth - kNK] = load_v(st_v, ks + kDepth - kNK);
-      }
-      settle_s(s);
     };
     // Per-lane validity bits of a partial tile: bit i = element i is a retained position
     // (element i is token (i/4)*8 + g*4 + i%4 of the tile).
-    auto valid_bits = [&](int pos0, bool full) -> uint32_t {
-      if (full) return 0xFFFFu;
+    auto valid_bits = [&](int pos0) -> uint32_t {
       uint32_t m = 0;
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         m |= (uint32_t)retained(pos0 + (i >> 2) * 8 + g * 4 + (i & 3), L, p.S, p.W) << i;
       return m;
     };
-    // logit of element i in the log2 domain
-    auto logit = [&](float sv, int i, int stage, uint32_t vbits) -> float {
-      float x = sv * p.scale_log2;
-      if constexpr (FP8)
-        x *= *LDS_PTR(float, lds_scales + stage * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
-      return (vbits >> i) & 1 ? x : -INFINITY;
+    // Logits are used in the log2 domain relative to the reference: t = s * c - ref (one
+    // fused multiply-add).  A masked-out position gets the raw value that maps to t = -inf.
+    const float c = p.scale_log2;
+    const float masked_raw = c < 0.f ? INFINITY : -INFINITY;
+    // fp8: the fp32 scale of the token behind element i, and all sixteen applied to S^T
+    auto tok_scale = [&](int stage, int i) -> float {
+      return *LDS_PTR(float, lds_scales + stage * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
     };
-    auto weight = [&](float x, int i, int stage, float r, float& lsum) -> float {
-      float e = __builtin_amdgcn_exp2f(x - r);
-      lsum += e;
-      if constexpr (FP8)
-        e *= *LDS_PTR(float, lds_scales + stage * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
-      return e;
+    auto scale_logits = [&](f32x16& s, int stage) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {  // elements 4 q4 .. 4 q4 + 3 are four consecutive tokens
+        const f32x4 sc = *LDS_PTR(f32x4, lds_scales + stage * kScaleBytes + (q4 * 8 + g * 4) * 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s[q4 * 4 + k] *= sc[k];
+      }
+    };
+    auto mask_partial = [&](f32x16& s, int pos0) {
+      const uint32_t vbits = valid_bits(pos0);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = (vbits >> i) & 1 ? s[i] : masked_raw;
     };
 
     float ref = 0.f, l_run = 0.f;
@@ -358,36 +386,44 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 #pragma unroll 1
     for (int attempt = 0; attempt < 2; ++attempt) {
       if (attempt > 0) {
-        if (n_tiles > 0) issue_tile(0);
-        if (n_tiles > 1) issue_tile(1);
+        issue_tile(0);
+        issue_tile(1);
       }
 #pragma unroll
       for (int cb = 0; cb < kV / 32; ++cb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
-      float mx_all = -INFINITY;  // running maximum of this lane's logits
+      float mt_all = -INFINITY;  // running maximum of this lane's t = s * c - ref
 
       if (n_tiles > 0) {
-        bf16x8 pf[2], vf[kDepth];
+        bf16x8 pf[2], fr[kRing];
         f32x16 s;
 
         // ---- tile 0: S^T, reference, weights (no PV to overlap with yet) ----
         {
-          wait_tile(0);
+          wait_tile();
           __syncthreads();
-          if (n_tiles > 2) issue_tile(2);
-          qk_tile(lds0, s, vf, lds0);
-          const int pos0 = tile_pos(0);
-          const uint32_t vbits = valid_bits(pos0, tile_full(pos0));
+          launder_offsets();
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            s[i] = logit(s[i], i, 0, vbits);
-            mx_all = fmaxf(mx_all, s[i]);
+          for (int d = 0; d < kRing; ++d) fr[d] = load_k(lds0, d);
+          issue_tile(2);
+#pragma unroll
+          for (int m = 0; m < kNK; ++m) {
+            if (m == 0) mfma_s_first(s, fr[m % kRing], qf[m]);
+            else mfma_s(s, fr[m % kRing], qf[m]);
+            if (m + kRing < kNK) fr[m % kRing] = load_k(lds0, m + kRing);
           }
+          settle_s(s);
+          const int pos0 = tile_pos(0);
+          if constexpr (FP8) scale_logits(s, 0);
+          if (!tile_full(pos0)) mask_partial(s, pos0);
+          float mx = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[i] * c);
           if (ref_exact == ref_exact) {
             ref = ref_exact;
           } else {
-            const float m2 = fmaxf(mx_all, __shfl_xor(mx_all, 32));
+            const float m2 = fmaxf(mx, __shfl_xor(mx, 32));
             // An integer reference makes weights computed against different references
             // differ by exact powers of two, so their bf16 roundings agree between
             // different partitions of the same sequence.  (-inf only if the data itself
@@ -396,36 +432,71 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           }
           float lsum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) pf[i >> 3][i & 7] = (__bf16)weight(s[i], i, 0, ref, lsum);
+          for (int i = 0; i < 16; ++i) {
+            const float t = fmaf(s[i], c, -ref);
+            mt_all = fmaxf(mt_all, t);
+            float e = __builtin_amdgcn_exp2f(t);
+            lsum += e;
+            if constexpr (FP8) e *= tok_scale(0, i);
+            pf[i >> 3][i & 7] = (__bf16)e;
+          }
           l_run = lsum;
         }
 
-        // ---- tiles 1 .. n-1: S^T of tile `it`, then PV of tile it-1 interleaved with the
-        //      softmax arithmetic of tile `it` ----
+        // ---- tiles 1 .. n-1: S^T of tile `it`, then PV of tile it-1 with the softmax
+        //      arithmetic of tile `it` and the direct loads of tile it+2 spread between
+        //      its MFMAs.  With one wave per SIMD the wave's own instruction issue is the
+        //      scarce resource: everything besides the 68 MFMAs is kept to a minimum. ----
 #pragma unroll 1
         for (int it = 1; it < n_tiles; ++it) {
           const int stage = it & (kStages - 1);
           const uint32_t st = lds0 + stage * kStageBytes;
           const uint32_t st_prev = lds0 + ((it - 1) & (kStages - 1)) * kStageBytes;
-          wait_tile(it);
+          wait_tile();
           __syncthreads();  // tile `it` is visible; every wave is done with the stage tile it+2 goes to
-          if (it + 2 < n_tiles) issue_tile(it + 2);
-          qk_tile(st, s, vf, st_prev);
-          const int pos0 = tile_pos(it);
-          const uint32_t vbits = valid_bits(pos0, tile_full(pos0));
-          bf16x8 pn[2];
-          float lsum = 0.f;
+          launder_offsets();
+          auto frag = [&](int m) -> bf16x8 { return m < kNK ? load_k(st, m) : load_v(st_prev, m - kNK); };
 #pragma unroll
-          for (int j = 0; j < kNV; ++j) {
-            mfma_o(acc[j & 15], vf[j % kDepth], pf[j >> 4]);
-            if (j + kDepth < kNV) vf[j % kDepth] = load_v(st_prev, j + kDepth);
-            if ((j & 1) == 0) {  // one softmax element of tile `it` per two MFMAs of tile it-1
-              const int i = j >> 1;
-              const float x = logit(s[i], i, stage, vbits);
-              mx_all = fmaxf(mx_all, x);
-              pn[i >> 3][i & 7] = (__bf16)weight(x, i, stage, ref, lsum);
+          for (int d = 0; d < kRing; ++d) fr[d] = frag(d);
+          const TileSrc ts = prep_tile(it + 2);
+          const int pos0 = tile_pos(it);
+          const bool full = tile_full(pos0);
+          bf16x8 pn[2];
+          float lsum = 0.f, mt = -INFINITY;
+#pragma unroll
+          for (int m = 0; m < kNK + kNV; ++m) {
+            if (m == 0) mfma_s_first(s, fr[m % kRing], qf[m]);
+            else if (m < kNK) mfma_s(s, fr[m % kRing], qf[m]);
+            else mfma_o(acc[(m - kNK) & 15], fr[m % kRing], pf[(m - kNK) >> 4]);
+            if (m + kRing < kNK + kNV) fr[m % kRing] = frag(m + kRing);
+            // the direct loads of tile it+2, spread evenly over the MFMAs (at most one per MFMA)
+            {
+              const int k0 = (m * kDmaPerTile) / (kNK + kNV), k1 = ((m + 1) * kDmaPerTile) / (kNK + kNV);
+              if (k1 > k0) dma_piece(ts, k0);
+            }
+            const int j = m - kNK;
+            if (j == 0 && (FP8 || !full)) {  // wave-uniform; rare for a bf16 cache
+              settle_s(s);
+              if constexpr (FP8) scale_logits(s, stage);
+              if (!full) mask_partial(s, pos0);
+            }
+            // S^T may be read by the vector ALU 12 instructions after its last MFMA: the
+            // 16 softmax elements of tile `it` are spread over PV MFMAs 4 .. 31 of tile it-1
+            // (checked on the generated code at build time).
+            constexpr int kFirst = 4;
+            if (j >= kFirst) {
+              const int i = ((j - kFirst) * 16) / (kNV - kFirst), i1 = ((j + 1 - kFirst) * 16) / (kNV - kFirst);
+              if (i1 > i) {  // at most one element per MFMA
+                const float t = fmaf(s[i], c, -ref);
+                mt = fmaxf(mt, t);
+                float e = __builtin_amdgcn_exp2f(t);
+                lsum += e;
+                if constexpr (FP8) e *= tok_scale(stage, i);
+                pn[i >> 3][i & 7] = (__bf16)e;
+              }
             }
           }
+          mt_all = fmaxf(mt_all, mt);
           l_run += lsum;
           pf[0] = pn[0];
           pf[1] = pn[1];
@@ -434,27 +505,27 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         // ---- PV of the last tile ----
         {
           const uint32_t st_last = lds0 + ((n_tiles - 1) & (kStages - 1)) * kStageBytes;
-          if (n_tiles > 1) {  // its first fragments were not requested by a following S^T
+          launder_offsets();
 #pragma unroll
-            for (int d = 0; d < kDepth; ++d) vf[d] = load_v(st_last, d);
-          }
+          for (int d = 0; d < kRing; ++d) fr[d] = load_v(st_last, d);
 #pragma unroll
           for (int j = 0; j < kNV; ++j) {
-            mfma_o(acc[j & 15], vf[j % kDepth], pf[j >> 4]);
-            if (j + kDepth < kNV) vf[j % kDepth] = load_v(st_last, j + kDepth);
+            mfma_o(acc[j & 15], fr[j % kRing], pf[j >> 4]);
+            if (j + kRing < kNV) fr[j % kRing] = load_v(st_last, j + kRing);
           }
           settle_o(acc);  // the compiler may move the tile between registers right after this
         }
       }
+      wait_vm<0>();  // the junk-region loads issued for tiles past the end
 
       // Did any lane of the work group see a logit too far above its reference?
       if (tid == 0) *LDS_PTR(int, lds_flag) = 0;
       __syncthreads();  // also: all reads of the stages are done before they are reused
-      if (attempt == 0 && __any(mx_all - ref > kRefSlack) && lane == 0) *LDS_PTR(int, lds_flag) = 1;
+      if (attempt == 0 && __any(mt_all > kRefSlack) && lane == 0) *LDS_PTR(int, lds_flag) = 1;
       __syncthreads();
       if (*LDS_PTR(int, lds_flag) == 0) break;
-      const float m2 = fmaxf(mx_all, __shfl_xor(mx_all, 32));
-      ref_exact = m2 == -INFINITY ? 0.f : ceilf(m2);
+      const float m2 = fmaxf(mt_all, __shfl_xor(mt_all, 32));
+      ref_exact = m2 == -INFINITY ? 0.f : ref + ceilf(m2);
     }
 
     // ---- epilogue: normalise, transpose through LDS, write whole rows ----
@@ -561,32 +632,17 @@ static hipError_t set_lds_attr() {
 
 hipError_t init_kernels() {
   hipError_t e;
-  if ((e = set_lds_attr<1, false>()) != hipSuccess) return e;
-  if ((e = set_lds_attr<2, false>()) != hipSuccess) return e;
   if ((e = set_lds_attr<4, false>()) != hipSuccess) return e;
-  if ((e = set_lds_attr<1, true>()) != hipSuccess) return e;
-  if ((e = set_lds_attr<2, true>()) != hipSuccess) return e;
   if ((e = set_lds_attr<4, true>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
 hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream) {
   if (n_units <= 0) return hipSuccess;
+  if (waves != 4) return hipErrorInvalidValue;
   dim3 grid(n_units), block(waves * 64);
-#define OA_LAUNCH(W, F) \
-  hipLaunchKernelGGL((decode_kernel<W, F>), grid, block, kLdsBytes, stream, p)
-  if (!fp8) {
-    if (waves == 4) OA_LAUNCH(4, false);
-    else if (waves == 2) OA_LAUNCH(2, false);
-    else if (waves == 1) OA_LAUNCH(1, false);
-    else return hipErrorInvalidValue;
-  } else {
-    if (waves == 4) OA_LAUNCH(4, true);
-    else if (waves == 2) OA_LAUNCH(2, true);
-    else if (waves == 1) OA_LAUNCH(1, true);
-    else return hipErrorInvalidValue;
-  }
-#undef OA_LAUNCH
+  if (!fp8) hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, kLdsBytes, stream, p);
+  else hipLaunchKernelGGL((decode_kernel<4, true>), grid, block, kLdsBytes, stream, p);
   return hipGetLastError();
 }
 

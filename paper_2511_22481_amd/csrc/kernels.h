@@ -33,7 +33,7 @@ struct CombineParams {
 
 // One-time per-process kernel attribute setup (large dynamic LDS).
 hipError_t init_kernels();
-// waves in {1, 2, 4}; grid = number of work units.
+// waves must be 4; grid = number of work units.
 hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream);
 hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t stream);
 

@@ -47,7 +47,7 @@ int fill_units(const std::vector<Item>& items, int cap, std::vector<Segment>* se
         if (load == 0) room = need;  // capacity smaller than one minimal segment
         else { close_unit(); continue; }
       }
-      int take = std::min(rem, room);
+      int take = std::min(std::min(rem, room), kMaxSegTiles);
       // avoid leaving a sliver behind
       if (rem - take > 0 && rem - take < kMinSegTiles) take = std::max(1, rem - kMinSegTiles);
       segs.push_back({it.b, it.hb, done, done + take, -1, (int32_t)unit_seg.size() - 1, 0,
@@ -87,8 +87,8 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
   hp.prob = prob;
   hp.num_cus = num_cus;
   hp.seq_lens.assign(seq_lens, seq_lens + prob.batch);
-  int waves_needed = (prob.num_heads + kHeadsPerWave - 1) / kHeadsPerWave;
-  hp.waves = waves_needed >= 4 ? 4 : (waves_needed >= 2 ? 2 : 1);
+  // Always four waves (one per SIMD), 32 heads each; waves past the last head idle along.
+  hp.waves = 4;
   hp.head_block = hp.waves * kHeadsPerWave;
   hp.n_hb = (prob.num_heads + hp.head_block - 1) / hp.head_block;
 
@@ -114,6 +114,7 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
     hp.unit_seg.assign(1, 0);
     for (const Item& it : items) {
       int pieces = std::max(1, std::min(prob.num_splits_hint, it.ntiles));
+      pieces = std::max(pieces, (it.ntiles + kMaxSegTiles - 1) / kMaxSegTiles);
       for (int s = 0; s < pieces; ++s) {
         int lo = (int)((int64_t)it.ntiles * s / pieces);
         int hi = (int)((int64_t)it.ntiles * (s + 1) / pieces);

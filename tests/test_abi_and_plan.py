@@ -118,7 +118,7 @@ def test_plan_headline_shapes():
 
 def test_split_hint_cuts_every_sequence():
     p = plan_for([32 * 40] * 3, 0, 1 << 20, hint=7)
-    assert p.max_splits == 7 and p.num_partials == 21 and p.num_units == 21
+    assert p.max_splits == 7 and p.num_partials == 21 and p.num_units == 21 and p.head_block == 128
     p = plan_for([32 * 2] * 3, 0, 1 << 20, hint=7)   # fewer tiles than pieces
     assert p.max_splits == 2
     p = plan_for([32 * 40] * 3, 0, 1 << 20, hint=1)
