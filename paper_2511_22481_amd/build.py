@@ -28,7 +28,7 @@ def build(force=True, verbose=False):
     is switched off for the device pass."""
     if not force and not is_stale():
         return LIB
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument", "-x", "hip"]
     cmd += [os.path.join(CSRC, f) for f in SOURCES]
@@ -52,7 +52,7 @@ def check_generated_code(verbose=False):
     from .check_isa import check
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "decode_kernels.s")
-        cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
+        cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++20",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument", "--cuda-device-only", "-S", "-x", "hip",
                os.path.join(CSRC, "decode_kernels.hip"), "-o", out]

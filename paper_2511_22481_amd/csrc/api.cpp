@@ -202,6 +202,7 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   dp.W = hp.prob.window;
   dp.head_block = hp.head_block;
   dp.out_fp32 = hp.prob.out_dtype == OMNIATTN_FP32;
+  dp.n_units = (int)hp.unit_seg.size() - 1;
   // A zero scale (uniform attention) is replaced by one too small to matter: the kernel
   // marks masked positions with an infinity that must survive the multiplication.
   dp.scale_log2 = hp.prob.softmax_scale * 1.4426950408889634f;

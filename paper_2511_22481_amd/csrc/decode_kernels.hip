@@ -21,6 +21,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "kernels.h"
 
@@ -59,9 +60,9 @@ constexpr int kTailBase = kTile * kMainRowBytes;                      // 32,768
 constexpr int kStageBytes = kTile * (kMainRowBytes + kTailRowBytes);  // 36,864
 constexpr int kStages = 4;
 constexpr int kScaleBytes = kTile * 4;  // per-token fp32 scales of one stage (fp8 cache)
-constexpr int kPageIdBytes = kMaxSegTiles * 4;  // physical page of every tile of the segment
-constexpr int kJunkBytes = 1024;  // target of the direct loads issued for tiles that do not exist
-constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16 + kPageIdBytes + kJunkBytes;  // 16: retry flag
+constexpr int kTileTabBytes = kMaxSegTiles * 8;  // first global byte of every tile of the segment
+constexpr int kJunkBytes = 4096;  // target of the direct loads issued for tiles that do not exist
+constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16 + kTileTabBytes + kJunkBytes;  // 16: retry flag
 __host__ __device__ constexpr int swz_main(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 __host__ __device__ constexpr int swz_tail(int r) { return (r >> 1) & 7; }
 // byte offset of chunk c (0..71) of row r inside a stage
@@ -106,31 +107,29 @@ __device__ __forceinline__ void settle_o(f32x16 (&acc)[kV / 32]) {
 }
 
 // Direct global->LDS load of 16 bytes per lane: lane l's bytes land at LDS address
-// lds_base + 16 l (lds_base wave-uniform), read from base + off (base wave-uniform,
-// off per lane).  Written as assembly so that the compiler does not treat it as a
-// store that may alias every later LDS read and drain the whole prefetch before the
-// first read of another stage; completion is awaited explicitly (wait_dma) before
-// the barrier that publishes the tile.
-__device__ __forceinline__ void dma16(const uint8_t* base, uint32_t off, uint32_t lds_base) {
-  // both are wave-uniform by construction; make that visible to the register allocator
+// M0 + IMM + 16 l and are read from base + off + IMM (base wave-uniform, off per lane;
+// the instruction's immediate offset applies to both sides).  Written as assembly so
+// that the compiler does not treat it as a store that may alias every later LDS read
+// and drain the whole prefetch before the first read of another stage; completion is
+// awaited explicitly (wait_vm) before the barrier that publishes the tile.
+// M0 carries the LDS base.  Nothing else in these kernels uses M0 (no indirect register
+// addressing, no GWS, no compiler-issued LDS-DMA), so it is simply overwritten.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma_set_lds_base(uint32_t lds_base) {
+  const uint32_t slds = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(slds) : "m0");
+}
+template <int IMM>
+__device__ __forceinline__ void dma16(const uint8_t* base, uint32_t off) {
+  // wave-uniform by construction; make that visible to the register allocator
   const uint64_t b = (uint64_t)(uintptr_t)base;
   const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
   const uint32_t b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
   const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
-  const uint32_t slds = __builtin_amdgcn_readfirstlane(lds_base);
-  // M0 carries the LDS base.  Nothing else in these kernels uses M0 (no indirect register
-  // addressing, no GWS, no compiler-issued LDS-DMA), so it is simply overwritten.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-  asm volatile(
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %0, %1"
-      :
-      : "v"(off), "s"(sbase), "s"(slds)
-      : "m0");
-#pragma clang diagnostic pop
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(sbase), "n"(IMM) : "m0");
 }
+#pragma clang diagnostic pop
 // Wait until at most N of this wave's vector-memory operations are outstanding.
 template <int N>
 __device__ __forceinline__ void wait_vm() {
@@ -146,6 +145,7 @@ __device__ __forceinline__ void wait_vm() {
 // summing a million terms) the work group runs the same segment code a second time
 // with r = that exact maximum, which cannot overflow.
 constexpr float kRefSlack = 64.f;
+constexpr int kXcds = 8;  // accelerator complex dies: work group i runs on XCD i % 8
 
 template <int WAVES, bool FP8>
 __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
@@ -153,8 +153,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds_raw;  // LDS byte address of stage 0
   const uint32_t lds_scales = lds0 + kStages * kStageBytes;
   const uint32_t lds_flag = lds_scales + kStages * kScaleBytes;
-  const uint32_t lds_pages = lds_flag + 16;
-  const uint32_t lds_junk = lds_pages + kPageIdBytes;
+  const uint32_t lds_tiles = lds_flag + 16;
+  const uint32_t lds_junk = lds_tiles + kTileTabBytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -184,7 +184,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   constexpr int kRowsPerWave = kTile / WAVES;                  // 8, 16 or 32
   constexpr int kDmaPerTile = kRowsPerWave + kRowsPerWave / 8;  // direct loads per wave and tile
 
-  const int unit = blockIdx.x;
+  // Work groups are dealt to the eight XCDs round-robin.  Consecutive work units (the
+  // pieces of one sequence, which read the same Q and neighbouring pages) are mapped to
+  // work groups of one XCD so that they share its L2.
+  const int per_xcd = (p.n_units + kXcds - 1) / kXcds;
+  const int unit = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  if (unit >= p.n_units) return;
   const int seg_lo = p.unit_seg[unit], seg_hi = p.unit_seg[unit + 1];
 
   for (int si = seg_lo; si < seg_hi; ++si) {
@@ -218,15 +223,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       ts.lmain = ts.ltail = lds_junk;
       ts.mstride = ts.tstride = 0;
       if (it >= n_tiles) return ts;
-      const int pos0 = tile_pos(it);
-      const int page = __builtin_amdgcn_readfirstlane(*LDS_PTR(int, lds_pages + it * 4));
-      const int slot0 = pos0 & (kPage - 1);
-      const bool full = tile_full(pos0);
+      // table entry: first global byte of the tile's rows; bit 0 = every position retained
+      const u32x2 e = *LDS_PTR(u32x2, lds_tiles + it * 8);
+      const uint32_t e_lo = __builtin_amdgcn_readfirstlane(e.x), e_hi = __builtin_amdgcn_readfirstlane(e.y);
+      const bool full = e_lo & 1;
+      const uint8_t* gbase = (const uint8_t*)(uintptr_t)(((uint64_t)e_hi << 32) | (e_lo & ~1u));
       const int stage = it & (kStages - 1);
       const uint32_t lbase = lds0 + stage * kStageBytes;
       const int row_w0 = wave * kRowsPerWave;
       if constexpr (!FP8) {
-        const uint8_t* gbase = p.kv + ((size_t)page * kPage + slot0) * kRowBytes;
         if (full) {
           ts.gbase = gbase;
           ts.lmain = lbase;
@@ -236,6 +241,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         } else {
           // partial tile: rows outside the retained set are zero-filled, never loaded
           // (their contents are unspecified and 0 * NaN would poison the PV product)
+          const int pos0 = tile_pos(it);
 #pragma unroll 1
           for (int ci = lane; ci < kRowsPerWave * kChunksPerRow; ci += 64) {
             const int r = ci / kChunksPerRow;
@@ -250,7 +256,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         // fp8 rows: 36 chunks of 16 codes; every code is widened exactly to bf16 and the
         // token's fp32 scale is kept aside: it multiplies the logit (after QK^T) and the
         // softmax weight (before PV), both in fp32, so dequantisation adds no rounding.
-        const uint8_t* gbase = p.kv + ((size_t)page * kPage + slot0) * kQK;
+        const int pos0 = tile_pos(it);
+        const float* sbase = p.kv_scales + (gbase - p.kv) / kQK;
         constexpr int n_chunks = kTile * (kQK / 16);  // 1152
 #pragma unroll 1
         for (int ci = tid; ci < n_chunks; ci += WAVES * 64) {
@@ -273,39 +280,58 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         }
         if (tid < kTile) {
           const bool ok = full || retained(pos0 + tid, L, p.S, p.W);
-          const float sc = ok ? p.kv_scales[(size_t)page * kPage + slot0 + tid] : 0.f;
-          *LDS_PTR(float, lds_scales + stage * kScaleBytes + tid * 4) = sc;
+          *LDS_PTR(float, lds_scales + stage * kScaleBytes + tid * 4) = ok ? sbase[tid] : 0.f;
         }
       }
       return ts;
     };
-    // Direct load number k (0 .. kDmaPerTile-1) of a prepared tile.  The per-lane offsets
-    // are recomputed each time (an XOR and a shift) from a lane id that went through an
-    // opaque move: kept alive across the MFMA loop they would cost registers it lacks.
-    auto dma_piece = [&](const TileSrc& ts, int k) {
-      uint32_t l = lane;
-      asm volatile("" : "+v"(l));
+    // Direct load number k (0 .. kDmaPerTile-1) of a prepared tile.  Four consecutive main
+    // rows share one LDS base (M0): the instruction's immediate offset (a multiple of the
+    // 1024-byte LDS row) selects the row on the LDS side and is subtracted from the lane's
+    // global offset.  The per-lane offset costs one XOR-and-add per load, computed from a
+    // lane id that went through an opaque move: kept alive across the MFMA loop as loop
+    // invariants the offsets would cost registers the loop does not have.
+    auto dma_piece = [&](const TileSrc& ts, auto k_tag) {
+      constexpr int k = decltype(k_tag)::value;
+      uint32_t l16 = lane << 4;
+      asm volatile("" : "+v"(l16));
       const int row_w0 = wave * kRowsPerWave;
-      if (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
+      if constexpr (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
+        constexpr int imm = (k & 3) * kMainRowBytes;
         const int row = row_w0 + k;
-        dma16(ts.gbase, row * kRowBytes + ((l ^ swz_main(row)) << 4), ts.lmain + row * ts.mstride);
+        if constexpr ((k & 3) == 0) dma_set_lds_base(ts.lmain + row * ts.mstride);
+        dma16<imm>(ts.gbase, (l16 ^ (swz_main(row) << 4)) + (row * kRowBytes - imm));
       } else {  // tail part: one instruction per 8 rows; lane l fetches row l / 8, rope chunk (l & 7) ^ swz
         const int r8 = row_w0 + 8 * (k - kRowsPerWave);
-        const uint32_t row = r8 + (l >> 3);
-        dma16(ts.gbase, row * kRowBytes + ((64 + ((l & 7) ^ swz_tail(row))) << 4), ts.ltail + r8 * ts.tstride);
+        const uint32_t row = r8 + (lane >> 3);
+        dma_set_lds_base(ts.ltail + r8 * ts.tstride);
+        dma16<0>(ts.gbase, row * kRowBytes + ((64 + ((lane & 7) ^ swz_tail(row))) << 4));
       }
     };
     auto issue_tile = [&](int it) {
       const TileSrc ts = prep_tile(it);
-#pragma unroll
-      for (int k = 0; k < kDmaPerTile; ++k) dma_piece(ts, k);
+      [&]<int... K>(std::integer_sequence<int, K...>) {
+        (dma_piece(ts, std::integral_constant<int, K>{}), ...);
+      }(std::make_integer_sequence<int, kDmaPerTile>{});
     };
     // Wait for this wave's share of a tile: only the loads of the tile after it may still
     // be in flight.
     auto wait_tile = [&]() { wait_vm<kDmaPerTile>(); };
 
+    // The page-table entries of the segment's tiles are requested first and the Q
+    // fragments right behind them, so that Q travels while the tile table is built and
+    // the first tiles are fetched.
+    // Table: first global byte of every tile (bit 0: whole tile retained), kept in LDS: the
+    // loop then needs no global load of its own besides the direct tile loads, whose
+    // completion counter must not be disturbed by other vector-memory waits.
+    constexpr int kTabPerThread = kMaxSegTiles / (WAVES * 64);
+    int page_of[kTabPerThread];
+#pragma unroll
+    for (int u = 0; u < kTabPerThread; ++u) {
+      const int t = tid + u * WAVES * 64;
+      page_of[u] = t < n_tiles ? p.page_table[(size_t)sg.b * p.max_pages + (tile_pos(t) >> 7)] : 0;
+    }
     // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
-    // Requested first; the page ids below and the first tiles travel at the same time.
     bf16x8 qf[kQK / 16];
     {
       // heads past H (a partly filled wave) read the last real head; their results are never written
@@ -314,11 +340,16 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       for (int ks = 0; ks < kQK / 16; ++ks)
         qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
     }
-    // Physical page of every tile of the segment, gathered once into LDS: the loop then
-    // needs no global load of its own besides the direct tile loads (whose completion
-    // counter must not be disturbed by other vector-memory waits).
-    for (int t = tid; t < n_tiles; t += WAVES * 64)
-      *LDS_PTR(int, lds_pages + t * 4) = p.page_table[(size_t)sg.b * p.max_pages + (tile_pos(t) >> 7)];
+#pragma unroll
+    for (int u = 0; u < kTabPerThread; ++u) {
+      const int t = tid + u * WAVES * 64;
+      if (t < n_tiles) {
+        const int pos0 = tile_pos(t);
+        const uint64_t a = (uint64_t)(uintptr_t)p.kv +
+                           ((uint64_t)page_of[u] * kPage + (pos0 & (kPage - 1))) * (FP8 ? kQK : kRowBytes);
+        *LDS_PTR(u32x2, lds_tiles + t * 8) = u32x2{(uint32_t)a | (uint32_t)tile_full(pos0), (uint32_t)(a >> 32)};
+      }
+    }
     __syncthreads();
     issue_tile(0);
     issue_tile(1);
@@ -331,21 +362,42 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     // the LDS reads are software-pipelined by hand through one ring of kRing fragments:
     // the MFMAs of an iteration (36 for S^T of tile `it`, then 32 for PV of tile it-1)
     // consume the ring in order and each fragment is requested kRing MFMAs ahead.
-    // The XORed per-lane offsets are recomputed at every use (one vector-ALU op): kept as
-    // loop invariants they would cost eight more registers than the loop can spare, and a
-    // spilled register's reload waits on the vector-memory counter, which would drain the
-    // tile prefetch.  The bases pass through an opaque move once per tile for that reason.
+    // LDS read addresses.  For a tile, 12 K-fragment and 8 V-fragment address registers
+    // are formed once (XOR of the swizzle-dependent field, plus the stage base); every read
+    // then only adds an immediate.  They are rebuilt per tile from bases that pass through
+    // an opaque move, so that the compiler neither keeps them alive across tiles nor
+    // spills them (a spill reload waits on the vector-memory counter and would drain the
+    // tile prefetch).
     uint32_t am = a_main, at = a_tail, vb0 = v_base[0], vb1 = v_base[1];
     auto launder_offsets = [&]() { asm volatile("" : "+v"(am), "+v"(at), "+v"(vb0), "+v"(vb1)); };
-    auto load_k = [&](uint32_t st, int ks) -> bf16x8 {
-      if (ks < 32) return *LDS_PTR(bf16x8, st + (am ^ ((ks & 7) << 5)) + (ks >> 3) * 256);
-      return *LDS_PTR(bf16x8, st + (at ^ ((ks - 32) << 5)));
+    struct KAddr { uint32_t a[12]; };
+    struct VAddr { uint32_t a[8]; };
+    auto k_addr = [&](uint32_t st) -> KAddr {
+      KAddr r;
+#pragma unroll
+      for (int b = 0; b < 8; ++b) r.a[b] = (am ^ (b << 5)) + st;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) r.a[8 + b] = (at ^ (b << 5)) + st;
+      return r;
     };
-    auto load_v = [&](uint32_t st, int j) -> bf16x8 {  // j = th * 16 + cb
+    auto v_addr = [&](uint32_t st) -> VAddr {
+      VAddr r;
+#pragma unroll
+      for (int cl = 0; cl < 4; ++cl) {
+        r.a[cl] = (vb0 ^ (cl << 6)) + st;
+        r.a[4 + cl] = (vb1 ^ (cl << 6)) + st;
+      }
+      return r;
+    };
+    auto load_k = [&](const KAddr& ka, int ks) -> bf16x8 {
+      if (ks < 32) return *LDS_PTR(bf16x8, ka.a[ks & 7] + (ks >> 3) * 256);
+      return *LDS_PTR(bf16x8, ka.a[8 + ks - 32]);
+    };
+    auto load_v = [&](const VAddr& va, int j) -> bf16x8 {  // j = th * 16 + cb
       const int th = j >> 4, cb = j & 15;
-      const uint32_t base = st + th * 16 * kMainRowBytes + (cb >> 2) * 256;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (vb0 ^ ((cb & 3) << 6))));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + (vb1 ^ ((cb & 3) << 6))));
+      const uint32_t imm = th * 16 * kMainRowBytes + (cb >> 2) * 256;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, va.a[cb & 3] + imm));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, va.a[4 + (cb & 3)] + imm));
       return __builtin_bit_cast(bf16x8, s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
     };
     // Per-lane validity bits of a partial tile: bit i = element i is a retained position
@@ -404,14 +456,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           wait_tile();
           __syncthreads();
           launder_offsets();
+          const KAddr ka = k_addr(lds0);
 #pragma unroll
-          for (int d = 0; d < kRing; ++d) fr[d] = load_k(lds0, d);
+          for (int d = 0; d < kRing; ++d) fr[d] = load_k(ka, d);
           issue_tile(2);
 #pragma unroll
           for (int m = 0; m < kNK; ++m) {
             if (m == 0) mfma_s_first(s, fr[m % kRing], qf[m]);
             else mfma_s(s, fr[m % kRing], qf[m]);
-            if (m + kRing < kNK) fr[m % kRing] = load_k(lds0, m + kRing);
+            if (m + kRing < kNK) fr[m % kRing] = load_k(ka, m + kRing);
           }
           settle_s(s);
           const int pos0 = tile_pos(0);
@@ -455,38 +508,40 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           wait_tile();
           __syncthreads();  // tile `it` is visible; every wave is done with the stage tile it+2 goes to
           launder_offsets();
-          auto frag = [&](int m) -> bf16x8 { return m < kNK ? load_k(st, m) : load_v(st_prev, m - kNK); };
+          const KAddr ka = k_addr(st);
+          const VAddr va = v_addr(st_prev);
+          auto frag = [&](int m) -> bf16x8 { return m < kNK ? load_k(ka, m) : load_v(va, m - kNK); };
 #pragma unroll
           for (int d = 0; d < kRing; ++d) fr[d] = frag(d);
           const TileSrc ts = prep_tile(it + 2);
-          const int pos0 = tile_pos(it);
-          const bool full = tile_full(pos0);
+          const bool full = *LDS_PTR(uint32_t, lds_tiles + it * 8) & 1;
           bf16x8 pn[2];
           float lsum = 0.f, mt = -INFINITY;
-#pragma unroll
-          for (int m = 0; m < kNK + kNV; ++m) {
-            if (m == 0) mfma_s_first(s, fr[m % kRing], qf[m]);
-            else if (m < kNK) mfma_s(s, fr[m % kRing], qf[m]);
+          // one MFMA and what is issued behind it; M is a compile-time constant
+          auto step = [&](auto m_tag) {
+            constexpr int m = decltype(m_tag)::value;
+            if constexpr (m == 0) mfma_s_first(s, fr[m % kRing], qf[m]);
+            else if constexpr (m < kNK) mfma_s(s, fr[m % kRing], qf[m]);
             else mfma_o(acc[(m - kNK) & 15], fr[m % kRing], pf[(m - kNK) >> 4]);
-            if (m + kRing < kNK + kNV) fr[m % kRing] = frag(m + kRing);
+            if constexpr (m + kRing < kNK + kNV) fr[m % kRing] = frag(m + kRing);
             // the direct loads of tile it+2, spread evenly over the MFMAs (at most one per MFMA)
-            {
-              const int k0 = (m * kDmaPerTile) / (kNK + kNV), k1 = ((m + 1) * kDmaPerTile) / (kNK + kNV);
-              if (k1 > k0) dma_piece(ts, k0);
-            }
-            const int j = m - kNK;
-            if (j == 0 && (FP8 || !full)) {  // wave-uniform; rare for a bf16 cache
-              settle_s(s);
-              if constexpr (FP8) scale_logits(s, stage);
-              if (!full) mask_partial(s, pos0);
+            constexpr int k0 = (m * kDmaPerTile) / (kNK + kNV), k1 = ((m + 1) * kDmaPerTile) / (kNK + kNV);
+            if constexpr (k1 > k0) dma_piece(ts, std::integral_constant<int, k0>{});
+            constexpr int j = m - kNK;
+            if constexpr (j == 0) {
+              if (FP8 || !full) {  // wave-uniform; rare for a bf16 cache
+                settle_s(s);
+                if constexpr (FP8) scale_logits(s, stage);
+                if (!full) mask_partial(s, tile_pos(it));
+              }
             }
             // S^T may be read by the vector ALU 12 instructions after its last MFMA: the
             // 16 softmax elements of tile `it` are spread over PV MFMAs 4 .. 31 of tile it-1
             // (checked on the generated code at build time).
             constexpr int kFirst = 4;
-            if (j >= kFirst) {
-              const int i = ((j - kFirst) * 16) / (kNV - kFirst), i1 = ((j + 1 - kFirst) * 16) / (kNV - kFirst);
-              if (i1 > i) {  // at most one element per MFMA
+            if constexpr (j >= kFirst) {
+              constexpr int i = ((j - kFirst) * 16) / (kNV - kFirst), i1 = ((j + 1 - kFirst) * 16) / (kNV - kFirst);
+              if constexpr (i1 > i) {  // at most one element per MFMA
                 const float t = fmaf(s[i], c, -ref);
                 mt = fmaxf(mt, t);
                 float e = __builtin_amdgcn_exp2f(t);
@@ -495,7 +550,10 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
                 pn[i >> 3][i & 7] = (__bf16)e;
               }
             }
-          }
+          };
+          [&]<int... M>(std::integer_sequence<int, M...>) {
+            (step(std::integral_constant<int, M>{}), ...);
+          }(std::make_integer_sequence<int, kNK + kNV>{});
           mt_all = fmaxf(mt_all, mt);
           l_run += lsum;
           pf[0] = pn[0];
@@ -506,12 +564,13 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         {
           const uint32_t st_last = lds0 + ((n_tiles - 1) & (kStages - 1)) * kStageBytes;
           launder_offsets();
+          const VAddr va = v_addr(st_last);
 #pragma unroll
-          for (int d = 0; d < kRing; ++d) fr[d] = load_v(st_last, d);
+          for (int d = 0; d < kRing; ++d) fr[d] = load_v(va, d);
 #pragma unroll
           for (int j = 0; j < kNV; ++j) {
             mfma_o(acc[j & 15], fr[j % kRing], pf[j >> 4]);
-            if (j + kRing < kNV) fr[j % kRing] = load_v(st_last, j + kRing);
+            if (j + kRing < kNV) fr[j % kRing] = load_v(va, j + kRing);
           }
           settle_o(acc);  // the compiler may move the tile between registers right after this
         }
@@ -640,7 +699,8 @@ hipError_t init_kernels() {
 hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream) {
   if (n_units <= 0) return hipSuccess;
   if (waves != 4) return hipErrorInvalidValue;
-  dim3 grid(n_units), block(waves * 64);
+  // the grid is rounded up to a multiple of the XCD count (see the unit mapping in the kernel)
+  dim3 grid(((n_units + kXcds - 1) / kXcds) * kXcds), block(waves * 64);
   if (!fp8) hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, kLdsBytes, stream, p);
   else hipLaunchKernelGGL((decode_kernel<4, true>), grid, block, kLdsBytes, stream, p);
   return hipGetLastError();

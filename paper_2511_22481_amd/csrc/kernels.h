@@ -18,7 +18,7 @@ struct DecodeParams {
   float* part_lse;  // [n_slots, head_block]
   const int32_t* unit_seg;
   const Segment* segs;
-  int H, max_pages, S, W, head_block, out_fp32;
+  int H, max_pages, S, W, head_block, out_fp32, n_units;
   float scale_log2;  // softmax_scale * log2(e)
 };
 

@@ -27,7 +27,7 @@ constexpr int kQK = OMNIATTN_QK_DIM;
 constexpr int kV = OMNIATTN_V_DIM;
 constexpr int kPage = OMNIATTN_PAGE;
 constexpr int kHeadsPerWave = 32;
-constexpr int kMaxSegTiles = 2048;  // tiles per segment (the kernel keeps their page ids in LDS)
+constexpr int kMaxSegTiles = 1024;  // tiles per segment (the kernel keeps a table of them in LDS)
 
 struct TileLayout {
   int ns;   // tiles [0, ns) cover the sink range
