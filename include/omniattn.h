@@ -134,7 +134,8 @@ int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t til
  *   out        device, out_dtype [B, H, 512]
  *   lse        device, fp32 [B, H]: natural-log sum of exp(scale * q.k_j) over
  *              the retained j.  An empty retained set gives out = 0, lse = -inf.
- *   workspace  device, at least omniattn_plan_workspace_bytes(plan) bytes,
+ *   workspace  device, at least omniattn_plan_workspace_bytes(plan) bytes (partial
+ *              rows of split sequences, in the output type, and their lse),
  *              256-byte aligned; may be NULL when that is 0.  Two decodes in
  *              flight at once need two workspaces.
  *

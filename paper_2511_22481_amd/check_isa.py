@@ -48,7 +48,32 @@ def check(asm_text, kernel_filter="decode_kernel"):
             block, name = [], line
         elif line:
             block.append(line)
-    # 2. MFMA results read too early
+    # 2. the first attempt's wait for tile 0 is `vmcnt(45)`: it leaves tile 1's 9 direct loads
+    #    and the 36 Q loads in flight.  That is only enough if at least 45 vector-memory
+    #    instructions follow tile 0's last direct load, i.e. if the compiler kept the Q loads
+    #    behind the direct loads of tiles 0 and 1: in program order the kernel's first 18
+    #    direct loads must be followed by 36 16-byte vector loads before the next direct load.
+    lines = [raw.split(";")[0].strip() for raw in asm_text.splitlines()]
+    in_k, n_dma, n_q, has_wait, kname = False, 0, 0, False, None
+
+    def close_kernel():
+        if in_k and has_wait and n_q < 36:
+            problems.append(f"{kname} first-tile wait assumes 36 Q loads behind the first 18 direct loads; "
+                            f"found {n_q}")
+    for line in lines + ["end:"]:
+        if line.endswith(":") and not line.startswith("."):
+            close_kernel()
+            in_k, n_dma, n_q, has_wait, kname = kernel_filter in line, 0, 0, False, line
+        if not in_k:
+            continue
+        op = line.split(" ")[0] if line else ""
+        if op.startswith("global_load_lds"):
+            n_dma += 1
+        elif op == "global_load_dwordx4" and n_dma == 18:
+            n_q += 1
+        elif line.startswith("s_waitcnt vmcnt(45)"):
+            has_wait = True
+    # 3. MFMA results read too early
     in_kernel = False
     pending = {}  # register -> wait states elapsed since the MFMA that writes it
     for lineno, raw in enumerate(asm_text.splitlines(), 1):

@@ -192,8 +192,8 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   dp.page_table = page_table;
   dp.out = out;
   dp.lse = lse;
-  dp.part_o = (float*)workspace;
-  dp.part_lse = dp.part_o ? dp.part_o + (size_t)hp.n_slots * hp.head_block * kV : nullptr;
+  dp.part_lse = (float*)workspace;
+  dp.part_o = workspace ? (char*)workspace + hp.part_rows_offset : nullptr;
   dp.unit_seg = plan->d_unit_seg;
   dp.segs = plan->d_segs;
   dp.H = hp.prob.num_heads;

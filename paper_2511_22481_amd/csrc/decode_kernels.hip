@@ -158,28 +158,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
-  const int n32 = lane & 31;  // head within the wave's 32 (B / C column)
-  const int g = lane >> 5;    // k-group of the MFMA operands
-
-  // ---- per-lane LDS read offsets (relative to a stage) ----
-  // QK^T A operand: token row n32, chunk 2 ks + g.  For ks < 32 the chunk position is
-  // ((2 (ks & 7) + g) ^ swz) + 16 (ks >> 3); since 2 (ks & 7) has bit 0 clear, the byte
-  // offset is a_main ^ ((ks & 7) << 5) plus a constant.
-  const uint32_t a_main = n32 * kMainRowBytes + ((g ^ swz_main(n32)) << 4);
-  const uint32_t a_tail = kTailBase + n32 * kTailRowBytes + ((g ^ swz_tail(n32)) << 4);
-  // PV A operand (V^T): each 16-lane group reads a 4-token x 16-column block transposed.
-  // Lane row = 16 th + 8 hi + 4 g + (i16 >> 2); chunk = 4 cb + c_lane.
-  const int i16 = lane & 15;
-  const int c_lane = ((lane >> 4) & 1) * 2 + ((i16 & 3) >> 1);
-  const int half8 = (i16 & 1) * 8;
-  // Chunk position = ((cb & 3) * 4 + c_lane) ^ swz; the swizzle's upper two bits only touch
-  // the (cb & 3) field, so the byte offset is v_base[hi] ^ ((cb & 3) << 6) + (cb >> 2) * 256.
-  uint32_t v_base[2];  // [upper k-slots]
-#pragma unroll
-  for (int hi = 0; hi < 2; ++hi) {
-    const int r = hi * 8 + g * 4 + (i16 >> 2);
-    v_base[hi] = r * kMainRowBytes + ((c_lane ^ swz_main(r)) << 4) + half8;
-  }
+  // Per-lane values are derived anew in each phase of a segment from a lane id that went
+  // through an opaque move.  Computed once at kernel entry they would stay alive across the
+  // MFMA loop, which has no registers to spare: the compiler would spill them, and every
+  // spill reload waits for all vector-memory traffic, tile prefetches included.
+  auto fresh_lane = [&]() {
+    int l = lane;
+    asm volatile("" : "+v"(l));
+    return l;
+  };
 
   constexpr int kRowsPerWave = kTile / WAVES;                  // 8, 16 or 32
   constexpr int kDmaPerTile = kRowsPerWave + kRowsPerWave / 8;  // direct loads per wave and tile
@@ -196,8 +183,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const Segment sg = p.segs[si];
     const int L = sg.L;
     const int h0 = sg.hb * p.head_block + wave * kHeadsPerWave;  // wave's first head
-    const int head = h0 + n32;
-    const bool head_ok = head < p.H;
+    const int lane_s = fresh_lane();
+    const int n32 = lane_s & 31;  // head within the wave's 32 (B / C column)
+    const int g = lane_s >> 5;    // k-group of the MFMA operands
     const TileLayout tl = tile_layout(L, p.S, p.W);
     const int n_tiles = sg.tile_hi - sg.tile_lo;
     const int sink_end = p.S < L ? p.S : L;
@@ -303,9 +291,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         dma16<imm>(ts.gbase, (l16 ^ (swz_main(row) << 4)) + (row * kRowBytes - imm));
       } else {  // tail part: one instruction per 8 rows; lane l fetches row l / 8, rope chunk (l & 7) ^ swz
         const int r8 = row_w0 + 8 * (k - kRowsPerWave);
-        const uint32_t row = r8 + (lane >> 3);
+        const uint32_t row = r8 + (l16 >> 7);
         dma_set_lds_base(ts.ltail + r8 * ts.tstride);
-        dma16<0>(ts.gbase, row * kRowBytes + ((64 + ((lane & 7) ^ swz_tail(row))) << 4));
+        dma16<0>(ts.gbase, row * kRowBytes + ((64 + (((l16 >> 4) & 7) ^ swz_tail(row))) << 4));
       }
     };
     auto issue_tile = [&](int it) {
@@ -318,9 +306,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     // be in flight.
     auto wait_tile = [&]() { wait_vm<kDmaPerTile>(); };
 
-    // The page-table entries of the segment's tiles are requested first and the Q
-    // fragments right behind them, so that Q travels while the tile table is built and
-    // the first tiles are fetched.
+    // The page-table entries of the segment's tiles come first: the tile table and with it
+    // the first direct loads depend on them.
     // Table: first global byte of every tile (bit 0: whole tile retained), kept in LDS: the
     // loop then needs no global load of its own besides the direct tile loads, whose
     // completion counter must not be disturbed by other vector-memory waits.
@@ -330,15 +317,6 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     for (int u = 0; u < kTabPerThread; ++u) {
       const int t = tid + u * WAVES * 64;
       page_of[u] = t < n_tiles ? p.page_table[(size_t)sg.b * p.max_pages + (tile_pos(t) >> 7)] : 0;
-    }
-    // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
-    bf16x8 qf[kQK / 16];
-    {
-      // heads past H (a partly filled wave) read the last real head; their results are never written
-      const uint16_t* qrow = p.q + ((size_t)sg.b * p.H + (head_ok ? head : p.H - 1)) * kQK + g * 8;
-#pragma unroll
-      for (int ks = 0; ks < kQK / 16; ++ks)
-        qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
     }
 #pragma unroll
     for (int u = 0; u < kTabPerThread; ++u) {
@@ -354,6 +332,22 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     issue_tile(0);
     issue_tile(1);
 
+    // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
+    // Requested behind the first two tiles: kQLoads vector loads per wave, which the wait for
+    // tile 0 leaves in flight (the build checks that the compiler emitted exactly that many
+    // and no other vector-memory instruction in between); S^T of tile 0 then starts on the
+    // first fragments while the rest of Q is still arriving.
+    bf16x8 qf[kQK / 16];
+    {
+      // heads past H (a partly filled wave) read the last real head; their results are never written
+      const int head = h0 + n32;
+      const uint16_t* qrow = p.q + ((size_t)sg.b * p.H + (head < p.H ? head : p.H - 1)) * kQK + g * 8;
+#pragma unroll
+      for (int ks = 0; ks < kQK / 16; ++ks)
+        qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
+    }
+    constexpr int kQLoads = kQK / 16;
+
     constexpr int kRing = 8;            // LDS fragment requests kept in flight
     constexpr int kNK = kQK / 16;       // 36 MFMAs for S^T
     constexpr int kNV = 2 * (kV / 32);  // 32 MFMAs for O^T
@@ -368,7 +362,24 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     // an opaque move, so that the compiler neither keeps them alive across tiles nor
     // spills them (a spill reload waits on the vector-memory counter and would drain the
     // tile prefetch).
-    uint32_t am = a_main, at = a_tail, vb0 = v_base[0], vb1 = v_base[1];
+    // QK^T A operand: token row n32, chunk 2 ks + g.  For ks < 32 the chunk position is
+    // ((2 (ks & 7) + g) ^ swz) + 16 (ks >> 3); since 2 (ks & 7) has bit 0 clear, the byte
+    // offset is am ^ ((ks & 7) << 5) plus a constant.
+    uint32_t am = n32 * kMainRowBytes + ((g ^ swz_main(n32)) << 4);
+    uint32_t at = kTailBase + n32 * kTailRowBytes + ((g ^ swz_tail(n32)) << 4);
+    // PV A operand (V^T): each 16-lane group reads a 4-token x 16-column block transposed.
+    // Lane row = 16 th + 8 hi + 4 g + (i16 >> 2); chunk = 4 cb + c_lane.  Chunk position =
+    // ((cb & 3) * 4 + c_lane) ^ swz; the swizzle's upper two bits only touch the (cb & 3)
+    // field, so the byte offset is vb{hi} ^ ((cb & 3) << 6) + (cb >> 2) * 256.
+    uint32_t vb0, vb1;
+    {
+      const int i16 = lane_s & 15;
+      const int c_lane = ((lane_s >> 4) & 1) * 2 + ((i16 & 3) >> 1);
+      const int half8 = (i16 & 1) * 8;
+      const int r0 = g * 4 + (i16 >> 2), r1 = 8 + r0;
+      vb0 = r0 * kMainRowBytes + ((c_lane ^ swz_main(r0)) << 4) + half8;
+      vb1 = r1 * kMainRowBytes + ((c_lane ^ swz_main(r1)) << 4) + half8;
+    }
     auto launder_offsets = [&]() { asm volatile("" : "+v"(am), "+v"(at), "+v"(vb0), "+v"(vb1)); };
     struct KAddr { uint32_t a[12]; };
     struct VAddr { uint32_t a[8]; };
@@ -453,7 +464,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 
         // ---- tile 0: S^T, reference, weights (no PV to overlap with yet) ----
         {
-          wait_tile();
+          if (attempt == 0) wait_vm<kDmaPerTile + kQLoads>();  // tile 1 and Q may still be in flight
+          else wait_tile();
           __syncthreads();
           launder_offsets();
           const KAddr ka = k_addr(lds0);
@@ -580,7 +592,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       // Did any lane of the work group see a logit too far above its reference?
       if (tid == 0) *LDS_PTR(int, lds_flag) = 0;
       __syncthreads();  // also: all reads of the stages are done before they are reused
-      if (attempt == 0 && __any(mt_all > kRefSlack) && lane == 0) *LDS_PTR(int, lds_flag) = 1;
+      if (attempt == 0 && __any(mt_all > kRefSlack) && (tid & 63) == 0) *LDS_PTR(int, lds_flag) = 1;
       __syncthreads();
       if (*LDS_PTR(int, lds_flag) == 0) break;
       const float m2 = fmaxf(mt_all, __shfl_xor(mt_all, 32));
@@ -594,11 +606,17 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const bool final_out = sg.slot < 0;
     const uint32_t ost = lds0 + wave * kOutWaveBytes;  // this wave's staging rows
     const int heads_here = p.H - h0 < kHeadsPerWave ? p.H - h0 : kHeadsPerWave;  // may be <= 0
-    if (head_ok && g == 0) {
-      if (final_out) p.lse[(size_t)sg.b * p.H + head] = lse;
-      else p.part_lse[(size_t)sg.slot * p.head_block + wave * kHeadsPerWave + n32] = lse;
+    const int lane_e = fresh_lane();
+    const int n32e = lane_e & 31, ge = lane_e >> 5;
+    if (n32e < heads_here && ge == 0) {
+      if (final_out) p.lse[(size_t)sg.b * p.H + h0 + n32e] = lse;
+      else p.part_lse[(size_t)sg.slot * p.head_block + wave * kHeadsPerWave + n32e] = lse;
     }
-    if (final_out && !p.out_fp32) {
+    // rows go to the output tensor, or (a split sequence) to this segment's partial slot;
+    // both hold the output type
+    const size_t row0 = final_out ? (size_t)sg.b * p.H + h0
+                                  : (size_t)sg.slot * p.head_block + wave * kHeadsPerWave;
+    if (!p.out_fp32) {
       // bf16: one round, a staged row is the head's 512 outputs (1024 bytes)
 #pragma unroll
       for (int cb = 0; cb < kV / 32; ++cb)
@@ -606,19 +624,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         for (int i4 = 0; i4 < 4; ++i4) {
           bf16x4 v = {(__bf16)(acc[cb][i4 * 4] * inv), (__bf16)(acc[cb][i4 * 4 + 1] * inv),
                       (__bf16)(acc[cb][i4 * 4 + 2] * inv), (__bf16)(acc[cb][i4 * 4 + 3] * inv)};
-          *LDS_PTR(bf16x4, ost + n32 * kOutRowBytes + (cb * 32 + i4 * 8 + g * 4) * 2) = v;
+          *LDS_PTR(bf16x4, ost + n32e * kOutRowBytes + (cb * 32 + i4 * 8 + ge * 4) * 2) = v;
         }
-      uint8_t* dst = (uint8_t*)p.out + ((size_t)sg.b * p.H + h0) * (kV * 2) + lane * 16;
+      uint8_t* dst = (uint8_t*)(final_out ? p.out : p.part_o) + row0 * (kV * 2) + lane_e * 16;
 #pragma unroll 4
       for (int h = 0; h < heads_here; ++h)
-        *(u32x4*)(dst + (size_t)h * (kV * 2)) = *LDS_PTR(u32x4, ost + h * kOutRowBytes + lane * 16);
+        *(u32x4*)(dst + (size_t)h * (kV * 2)) = *LDS_PTR(u32x4, ost + h * kOutRowBytes + lane_e * 16);
     } else {
-      // fp32 rows (partials or fp32 output): two rounds of 256 columns
-      uint8_t* dst = final_out
-                         ? (uint8_t*)p.out + ((size_t)sg.b * p.H + h0) * (kV * 4)
-                         : (uint8_t*)p.part_o +
-                               ((size_t)sg.slot * p.head_block + wave * kHeadsPerWave) * (kV * 4);
-      dst += lane * 16;
+      // fp32 rows: two rounds of 256 columns
+      uint8_t* dst = (uint8_t*)(final_out ? p.out : p.part_o) + row0 * (kV * 4) + lane_e * 16;
 #pragma unroll
       for (int r = 0; r < 2; ++r) {
 #pragma unroll
@@ -628,12 +642,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             const int cb = r * 8 + cb8;
             f32x4 v = {acc[cb][i4 * 4] * inv, acc[cb][i4 * 4 + 1] * inv, acc[cb][i4 * 4 + 2] * inv,
                        acc[cb][i4 * 4 + 3] * inv};
-            *LDS_PTR(f32x4, ost + n32 * kOutRowBytes + (cb8 * 32 + i4 * 8 + g * 4) * 4) = v;
+            *LDS_PTR(f32x4, ost + n32e * kOutRowBytes + (cb8 * 32 + i4 * 8 + ge * 4) * 4) = v;
           }
 #pragma unroll 4
         for (int h = 0; h < heads_here; ++h)
           *(u32x4*)(dst + (size_t)h * (kV * 4) + r * 1024) =
-              *LDS_PTR(u32x4, ost + h * kOutRowBytes + lane * 16);
+              *LDS_PTR(u32x4, ost + h * kOutRowBytes + lane_e * 16);
       }
     }
     __syncthreads();  // staging rows are free again before the next segment's tiles arrive
@@ -660,12 +674,18 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
   for (int s = 0; s < it.nslots; ++s) {
     const size_t row = (size_t)(it.slot0 + s) * p.head_block + hl;
     const float w = expf(p.part_lse[row] - tot);
-    const f32x4* src = (const f32x4*)(p.part_o + row * kV + lane * 8);
-    f32x4 a = src[0], b = src[1];
+    if (p.out_fp32) {
+      const f32x4* src = (const f32x4*)((const float*)p.part_o + row * kV + lane * 8);
+      f32x4 a = src[0], b = src[1];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      o[k] += w * a[k];
-      o[4 + k] += w * b[k];
+      for (int k = 0; k < 4; ++k) {
+        o[k] += w * a[k];
+        o[4 + k] += w * b[k];
+      }
+    } else {
+      const bf16x8 a = *(const bf16x8*)((const uint16_t*)p.part_o + row * kV + lane * 8);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) o[k] += w * (float)a[k];
     }
   }
   const size_t orow = (size_t)it.b * p.H + head;

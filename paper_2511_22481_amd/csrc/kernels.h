@@ -14,7 +14,7 @@ struct DecodeParams {
   const int32_t* page_table;
   void* out;
   float* lse;
-  float* part_o;    // [n_slots, head_block, 512]
+  void* part_o;     // [n_slots, head_block, 512] in the output type (bf16 or fp32)
   float* part_lse;  // [n_slots, head_block]
   const int32_t* unit_seg;
   const Segment* segs;
@@ -24,7 +24,7 @@ struct DecodeParams {
 
 struct CombineParams {
   const CombineItem* items;
-  const float* part_o;
+  const void* part_o;
   const float* part_lse;
   void* out;
   float* lse;

@@ -151,8 +151,11 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
     i = j;
   }
   for (Segment& s : hp.segs) s.L = seq_lens[s.b];
-  size_t bytes = (size_t)hp.n_slots * hp.head_block * (kV + 1) * sizeof(float);
-  hp.workspace_bytes = (bytes + 255) & ~(size_t)255;
+  // workspace: lse of every partial row (fp32), then the partial rows in the output type
+  const size_t rows = (size_t)hp.n_slots * hp.head_block;
+  const size_t elt = prob.out_dtype == OMNIATTN_FP32 ? 4 : 2;
+  hp.part_rows_offset = (rows * sizeof(float) + 255) & ~(size_t)255;
+  hp.workspace_bytes = rows ? ((hp.part_rows_offset + rows * kV * elt + 255) & ~(size_t)255) : 0;
   return OMNIATTN_OK;
 }
 

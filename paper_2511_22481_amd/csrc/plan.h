@@ -77,6 +77,7 @@ struct HostPlan {
   std::vector<CombineItem> combine;
   int n_slots = 0;
   size_t workspace_bytes = 0;
+  size_t part_rows_offset = 0;  // byte offset of the partial rows inside the workspace
 };
 
 // Returns OMNIATTN_OK or an error code.

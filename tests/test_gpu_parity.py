@@ -79,11 +79,14 @@ def test_stress_logits(c):
 
 def test_fp32_output():
     inp = parity.to_device(make_custom(2, 64, [1000, 300], 64, 256, seed=5, q_std=1.0, kv_std=1.0))
-    out, lse, _ = parity.run_gpu(inp, out_dtype=torch.float32)
+    out, lse, plan = parity.run_gpu(inp, out_dtype=torch.float32)
     assert out.dtype == torch.float32
     e = parity.assert_parity(inp, out, lse, row_rel_l2=8e-3)
     out16, _, _ = parity.run_gpu(inp)
-    assert torch.equal(out.to(torch.bfloat16), out16)   # same arithmetic, only the rounding differs
+    if plan.num_partials == 0:   # same arithmetic, only the rounding differs (partials hold the output type)
+        assert torch.equal(out.to(torch.bfloat16), out16)
+    else:
+        assert float((out.to(torch.bfloat16).float() - out16.float()).abs().max()) <= 0.02 * float(out.abs().max())
 
 
 # ---------------------------------------------------------------------------- invariants ---
