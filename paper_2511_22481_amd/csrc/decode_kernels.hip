@@ -656,48 +656,71 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 
 // Merge the partial results of one (sequence, head block): out = sum_s w_s O_s with
 // w_s = exp(lse_s - lse), lse = log sum_s exp(lse_s).  One work group per
-// (combine item, group of 4 heads); 64 lanes x 8 columns cover one head row.
+// (combine item, group of 4 heads); 64 lanes x 8 columns cover one head row.  Partials
+// are taken four at a time, all their loads in flight together, and folded into a
+// running (maximum, sum, row) triple, so any number of partials takes one pass.
 __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
   const CombineItem it = p.items[blockIdx.x];
   const int hl = blockIdx.y * 4 + (threadIdx.x >> 6);
   const int head = it.hb * p.head_block + hl;
   if (hl >= p.head_block || head >= p.H) return;
   const int lane = threadIdx.x & 63;
-  float m = -INFINITY;
-  for (int s = 0; s < it.nslots; ++s)
-    m = fmaxf(m, p.part_lse[(size_t)(it.slot0 + s) * p.head_block + hl]);
-  float z = 0.f;
-  for (int s = 0; s < it.nslots; ++s)
-    z += expf(p.part_lse[(size_t)(it.slot0 + s) * p.head_block + hl] - m);
-  const float tot = m + logf(z);
+  constexpr int kBatch = 4;
+  float m = -INFINITY, z = 0.f;
   float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int s = 0; s < it.nslots; ++s) {
-    const size_t row = (size_t)(it.slot0 + s) * p.head_block + hl;
-    const float w = expf(p.part_lse[row] - tot);
-    if (p.out_fp32) {
-      const f32x4* src = (const f32x4*)((const float*)p.part_o + row * kV + lane * 8);
-      f32x4 a = src[0], b = src[1];
+  for (int s0 = 0; s0 < it.nslots; s0 += kBatch) {
+    float l[kBatch];
+    f32x4 ra[kBatch], rb[kBatch];
+    bf16x8 rh[kBatch];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        o[k] += w * a[k];
-        o[4 + k] += w * b[k];
+    for (int k = 0; k < kBatch; ++k) {
+      const bool ok = s0 + k < it.nslots;
+      const size_t row = (size_t)(it.slot0 + (ok ? s0 + k : 0)) * p.head_block + hl;
+      l[k] = ok ? p.part_lse[row] : -INFINITY;
+      if (p.out_fp32) {
+        const f32x4* src = (const f32x4*)((const float*)p.part_o + row * kV + lane * 8);
+        ra[k] = src[0];
+        rb[k] = src[1];
+      } else {
+        rh[k] = *(const bf16x8*)((const uint16_t*)p.part_o + row * kV + lane * 8);
       }
-    } else {
-      const bf16x8 a = *(const bf16x8*)((const uint16_t*)p.part_o + row * kV + lane * 8);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) o[k] += w * (float)a[k];
     }
+    float mb = m;
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) mb = fmaxf(mb, l[k]);
+    if (mb == -INFINITY) continue;  // nothing but empty partials so far
+    const float keep = __expf(m - mb);  // 0 on the first batch (m = -inf)
+    z *= keep;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] *= keep;
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const float w = __expf(l[k] - mb);  // 0 for a slot past the end
+      z += w;
+      if (p.out_fp32) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          o[c] = fmaf(w, ra[k][c], o[c]);
+          o[4 + c] = fmaf(w, rb[k][c], o[4 + c]);
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[c] = fmaf(w, (float)rh[k][c], o[c]);
+      }
+    }
+    m = mb;
   }
+  const float inv = z > 0.f ? 1.0f / z : 0.f;
   const size_t orow = (size_t)it.b * p.H + head;
-  if (lane == 0) p.lse[orow] = tot;
+  if (lane == 0) p.lse[orow] = z > 0.f ? m + __logf(z) : -INFINITY;
   if (p.out_fp32) {
     float* dst = (float*)p.out + orow * kV + lane * 8;
-    *(f32x4*)dst = f32x4{o[0], o[1], o[2], o[3]};
-    *(f32x4*)(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
+    *(f32x4*)dst = f32x4{o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
+    *(f32x4*)(dst + 4) = f32x4{o[4] * inv, o[5] * inv, o[6] * inv, o[7] * inv};
   } else {
     bf16x8 v;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = (__bf16)o[k];
+    for (int k = 0; k < 8; ++k) v[k] = (__bf16)(o[k] * inv);
     *(bf16x8*)((uint16_t*)p.out + orow * kV + lane * 8) = v;
   }
 }
