@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="independent input sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default=WORKLOAD)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run plain 1 GiB device copies (outside the timed region): the "
+                         "calibration kernel for HBM byte counters collected with rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by batch with no "
@@ -77,6 +80,14 @@ def main():
     def step(i):
         s = sets[i % len(sets)]
         oa.omniattn_decode(plan, s.q, s.kv_cache, s.kv_scales, s.page_table, out, lse, ws, stream)
+
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)

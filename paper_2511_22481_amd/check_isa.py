@@ -34,46 +34,25 @@ def _regs(text):
 def check(asm_text, kernel_filter="decode_kernel"):
     """Returns a list of violation strings (empty = fine)."""
     problems = []
-    # 1. no register spill traffic inside a basic block that runs a whole MFMA chain: a
-    #    spill reload waits on the vector-memory counter and would drain the tile prefetch
+    # 1. no register spill traffic inside a basic block that runs part of the MFMA stream: a
+    #    spill reload waits on the vector-memory counter and would drain the tile prefetch.
+    #    (Only the bf16-cache kernel prefetches tiles with direct loads; the fp8 kernel fills
+    #    its tiles through registers at the top of an iteration, so a reload there costs time
+    #    but drains nothing.)
     block, name, in_k = [], None, False
     for raw in asm_text.splitlines() + ["end:"]:
         line = raw.split(";")[0].strip()
         if line.endswith(":"):
-            if in_k and sum(l.startswith("v_mfma") for l in block) >= 60 and any(
-                    l.startswith("scratch_") for l in block):
-                problems.append(f"register spill traffic inside the MFMA loop of block {name}")
+            # (a spill access behind a block's last MFMAs, e.g. after the final PV, is harmless)
+            first = next((i for i, l in enumerate(block) if l.startswith("scratch_")), None)
+            if in_k and first is not None and sum(l.startswith("v_mfma") for l in block[first:]) >= 8:
+                problems.append(f"register spill traffic in front of MFMAs in block {name}")
             if not line.startswith("."):
-                in_k = kernel_filter in line
+                in_k = kernel_filter in line and "ELb1E" not in line
             block, name = [], line
         elif line:
             block.append(line)
-    # 2. the first attempt's wait for tile 0 is `vmcnt(45)`: it leaves tile 1's 9 direct loads
-    #    and the 36 Q loads in flight.  That is only enough if at least 45 vector-memory
-    #    instructions follow tile 0's last direct load, i.e. if the compiler kept the Q loads
-    #    behind the direct loads of tiles 0 and 1: in program order the kernel's first 18
-    #    direct loads must be followed by 36 16-byte vector loads before the next direct load.
-    lines = [raw.split(";")[0].strip() for raw in asm_text.splitlines()]
-    in_k, n_dma, n_q, has_wait, kname = False, 0, 0, False, None
-
-    def close_kernel():
-        if in_k and has_wait and n_q < 36:
-            problems.append(f"{kname} first-tile wait assumes 36 Q loads behind the first 18 direct loads; "
-                            f"found {n_q}")
-    for line in lines + ["end:"]:
-        if line.endswith(":") and not line.startswith("."):
-            close_kernel()
-            in_k, n_dma, n_q, has_wait, kname = kernel_filter in line, 0, 0, False, line
-        if not in_k:
-            continue
-        op = line.split(" ")[0] if line else ""
-        if op.startswith("global_load_lds"):
-            n_dma += 1
-        elif op == "global_load_dwordx4" and n_dma == 18:
-            n_q += 1
-        elif line.startswith("s_waitcnt vmcnt(45)"):
-            has_wait = True
-    # 3. MFMA results read too early
+    # 2. MFMA results read too early
     in_kernel = False
     pending = {}  # register -> wait states elapsed since the MFMA that writes it
     for lineno, raw in enumerate(asm_text.splitlines(), 1):

@@ -17,7 +17,7 @@ struct omniattn_plan_s {
   bool on_device = false;
   int device = -1;
   // device copies of the plan metadata (owned)
-  int32_t* d_unit_seg = nullptr;
+  UnitHeader* d_units = nullptr;
   Segment* d_segs = nullptr;
   CombineItem* d_combine = nullptr;
 };
@@ -42,10 +42,10 @@ std::once_flag g_init_once;
 hipError_t g_init_status = hipSuccess;
 
 void free_device(omniattn_plan_s* pl) {
-  if (pl->d_unit_seg) (void)hipFree(pl->d_unit_seg);
+  if (pl->d_units) (void)hipFree(pl->d_units);
   if (pl->d_segs) (void)hipFree(pl->d_segs);
   if (pl->d_combine) (void)hipFree(pl->d_combine);
-  pl->d_unit_seg = nullptr;
+  pl->d_units = nullptr;
   pl->d_segs = nullptr;
   pl->d_combine = nullptr;
 }
@@ -107,7 +107,14 @@ int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
   int rc = make_plan(&pl, prob, seq_lens_host, cus > 0 ? cus : 256);
   if (rc != OMNIATTN_OK) return rc;
   pl->device = dev;
-  rc = upload(&pl->d_unit_seg, pl->hp.unit_seg);
+  {
+    std::vector<UnitHeader> hdr(pl->hp.unit_seg.size() - 1);
+    for (size_t u = 0; u + 1 < pl->hp.unit_seg.size(); ++u) {
+      hdr[u] = UnitHeader{pl->hp.unit_seg[u], pl->hp.unit_seg[u + 1], 0, 0, Segment{}};
+      if (hdr[u].seg_lo < hdr[u].seg_hi) hdr[u].first = pl->hp.segs[hdr[u].seg_lo];
+    }
+    rc = upload(&pl->d_units, hdr);
+  }
   if (rc == OMNIATTN_OK) rc = upload(&pl->d_segs, pl->hp.segs);
   if (rc == OMNIATTN_OK) rc = upload(&pl->d_combine, pl->hp.combine);
   if (rc != OMNIATTN_OK) {
@@ -194,7 +201,7 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   dp.lse = lse;
   dp.part_lse = (float*)workspace;
   dp.part_o = workspace ? (char*)workspace + hp.part_rows_offset : nullptr;
-  dp.unit_seg = plan->d_unit_seg;
+  dp.units = plan->d_units;
   dp.segs = plan->d_segs;
   dp.H = hp.prob.num_heads;
   dp.max_pages = hp.prob.max_pages_per_seq;

@@ -177,10 +177,28 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const int per_xcd = (p.n_units + kXcds - 1) / kXcds;
   const int unit = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
   if (unit >= p.n_units) return;
-  const int seg_lo = p.unit_seg[unit], seg_hi = p.unit_seg[unit + 1];
+  // The unit's header (segment range and a copy of its first segment) in three 16-byte
+  // loads issued together; the values are wave-uniform and moved to scalar registers.
+  auto uniform4 = [](u32x4 v) {
+    return u32x4{(uint32_t)__builtin_amdgcn_readfirstlane(v.x), (uint32_t)__builtin_amdgcn_readfirstlane(v.y),
+                 (uint32_t)__builtin_amdgcn_readfirstlane(v.z), (uint32_t)__builtin_amdgcn_readfirstlane(v.w)};
+  };
+  static_assert(sizeof(UnitHeader) == 48 && sizeof(Segment) == 32, "header layout");
+  const u32x4* hdr = (const u32x4*)(p.units + unit);
+  const u32x4 hdr0 = hdr[0], hdr1 = hdr[1], hdr2 = hdr[2];
+  const int seg_lo = __builtin_amdgcn_readfirstlane(hdr0.x), seg_hi = __builtin_amdgcn_readfirstlane(hdr0.y);
 
   for (int si = seg_lo; si < seg_hi; ++si) {
-    const Segment sg = p.segs[si];
+    u32x4 sg_a = hdr1, sg_b = hdr2;
+    if (si != seg_lo) {
+      const u32x4* sp = (const u32x4*)(p.segs + si);
+      sg_a = sp[0];
+      sg_b = sp[1];
+    }
+    sg_a = uniform4(sg_a);
+    sg_b = uniform4(sg_b);
+    const Segment sg = {(int32_t)sg_a.x, (int32_t)sg_a.y, (int32_t)sg_a.z, (int32_t)sg_a.w,
+                        (int32_t)sg_b.x, (int32_t)sg_b.y, (int32_t)sg_b.z, (int32_t)sg_b.w};
     const int L = sg.L;
     const int h0 = sg.hb * p.head_block + wave * kHeadsPerWave;  // wave's first head
     const int lane_s = fresh_lane();
@@ -205,15 +223,13 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       uint32_t lmain, ltail;  // LDS destinations of row 0 (main part, tail part)
       uint32_t mstride, tstride;  // 1024 / 128, or 0 for the junk target
     };
-    auto prep_tile = [&](int it) -> TileSrc {
+    auto prep_tile_e = [&](int it, uint32_t e_lo, uint32_t e_hi) -> TileSrc {
       TileSrc ts;
       ts.gbase = (const uint8_t*)p.q;
       ts.lmain = ts.ltail = lds_junk;
       ts.mstride = ts.tstride = 0;
       if (it >= n_tiles) return ts;
       // table entry: first global byte of the tile's rows; bit 0 = every position retained
-      const u32x2 e = *LDS_PTR(u32x2, lds_tiles + it * 8);
-      const uint32_t e_lo = __builtin_amdgcn_readfirstlane(e.x), e_hi = __builtin_amdgcn_readfirstlane(e.y);
       const bool full = e_lo & 1;
       const uint8_t* gbase = (const uint8_t*)(uintptr_t)(((uint64_t)e_hi << 32) | (e_lo & ~1u));
       const int stage = it & (kStages - 1);
@@ -296,6 +312,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         dma16<0>(ts.gbase, row * kRowBytes + ((64 + (((l16 >> 4) & 7) ^ swz_tail(row))) << 4));
       }
     };
+    // Table entry of tile `it`.  The index is clamped to the table; entries at or past
+    // n_tiles are stale and never interpreted (prep_tile_e checks the index first).
+    auto tile_entry = [&](int it) -> u32x2 {
+      return *LDS_PTR(u32x2, lds_tiles + (it < kMaxSegTiles ? it : kMaxSegTiles - 1) * 8);
+    };
+    auto prep_tile = [&](int it) -> TileSrc {
+      const u32x2 e = tile_entry(it);
+      return prep_tile_e(it, __builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
+    };
     auto issue_tile = [&](int it) {
       const TileSrc ts = prep_tile(it);
       [&]<int... K>(std::integer_sequence<int, K...>) {
@@ -312,15 +337,36 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     // loop then needs no global load of its own besides the direct tile loads, whose
     // completion counter must not be disturbed by other vector-memory waits.
     constexpr int kTabPerThread = kMaxSegTiles / (WAVES * 64);
+    int tid_s = tid;  // per segment, see fresh_lane
+    asm volatile("" : "+v"(tid_s));
     int page_of[kTabPerThread];
+    // Unconditional loads, so that all of a thread's entries are requested together instead
+    // of one per branch: an index past the segment's tiles is clamped to its last tile, and
+    // a segment without tiles reads (and ignores) a word of the plan instead.
+    const int32_t* pt_row = n_tiles > 0 ? p.page_table + (size_t)sg.b * p.max_pages : (const int32_t*)p.units;
 #pragma unroll
     for (int u = 0; u < kTabPerThread; ++u) {
-      const int t = tid + u * WAVES * 64;
-      page_of[u] = t < n_tiles ? p.page_table[(size_t)sg.b * p.max_pages + (tile_pos(t) >> 7)] : 0;
+      const int t = tid_s + u * WAVES * 64;
+      const int tc = t < n_tiles ? t : n_tiles - 1;
+      page_of[u] = pt_row[n_tiles > 0 ? tile_pos(tc) >> 7 : 0];
     }
+    // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
+    // Requested right behind the page-table entries, so that they stream in while the tile
+    // table is built and the first direct loads are issued; they are older than those
+    // loads, so the wait for tile 0 covers them.
+    bf16x8 qf[kQK / 16];
+    auto load_q = [&]() {
+      // heads past H (a partly filled wave) read the last real head; their results are never written
+      const int head = h0 + n32;
+      const uint16_t* qrow = p.q + ((size_t)sg.b * p.H + (head < p.H ? head : p.H - 1)) * kQK + g * 8;
+#pragma unroll
+      for (int ks = 0; ks < kQK / 16; ++ks)
+        qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
+    };
+    load_q();
 #pragma unroll
     for (int u = 0; u < kTabPerThread; ++u) {
-      const int t = tid + u * WAVES * 64;
+      const int t = tid_s + u * WAVES * 64;
       if (t < n_tiles) {
         const int pos0 = tile_pos(t);
         const uint64_t a = (uint64_t)(uintptr_t)p.kv +
@@ -331,22 +377,6 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     __syncthreads();
     issue_tile(0);
     issue_tile(1);
-
-    // ---- Q fragments: B operand, lane (head n32, g) holds d = 16 ks + 8 g .. + 8 ----
-    // Requested behind the first two tiles: kQLoads vector loads per wave, which the wait for
-    // tile 0 leaves in flight (the build checks that the compiler emitted exactly that many
-    // and no other vector-memory instruction in between); S^T of tile 0 then starts on the
-    // first fragments while the rest of Q is still arriving.
-    bf16x8 qf[kQK / 16];
-    {
-      // heads past H (a partly filled wave) read the last real head; their results are never written
-      const int head = h0 + n32;
-      const uint16_t* qrow = p.q + ((size_t)sg.b * p.H + (head < p.H ? head : p.H - 1)) * kQK + g * 8;
-#pragma unroll
-      for (int ks = 0; ks < kQK / 16; ++ks)
-        qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
-    }
-    constexpr int kQLoads = kQK / 16;
 
     constexpr int kRing = 8;            // LDS fragment requests kept in flight
     constexpr int kNK = kQK / 16;       // 36 MFMAs for S^T
@@ -449,6 +479,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 #pragma unroll 1
     for (int attempt = 0; attempt < 2; ++attempt) {
       if (attempt > 0) {
+        // (Q is fetched again rather than kept alive across the whole first attempt)
+        load_q();
         issue_tile(0);
         issue_tile(1);
       }
@@ -459,24 +491,25 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       float mt_all = -INFINITY;  // running maximum of this lane's t = s * c - ref
 
       if (n_tiles > 0) {
+        // pf: bf16 weights of the previous tile (B operand of PV); fr: the ring of operand
+        // fragments requested ahead.
         bf16x8 pf[2], fr[kRing];
         f32x16 s;
 
         // ---- tile 0: S^T, reference, weights (no PV to overlap with yet) ----
         {
-          if (attempt == 0) wait_vm<kDmaPerTile + kQLoads>();  // tile 1 and Q may still be in flight
-          else wait_tile();
+          wait_tile();  // tile 1 may still be in flight; Q is older than tile 0
           __syncthreads();
           launder_offsets();
-          const KAddr ka = k_addr(lds0);
+          const KAddr ka0 = k_addr(lds0);
 #pragma unroll
-          for (int d = 0; d < kRing; ++d) fr[d] = load_k(ka, d);
+          for (int d = 0; d < kRing; ++d) fr[d] = load_k(ka0, d);
           issue_tile(2);
 #pragma unroll
           for (int m = 0; m < kNK; ++m) {
             if (m == 0) mfma_s_first(s, fr[m % kRing], qf[m]);
             else mfma_s(s, fr[m % kRing], qf[m]);
-            if (m + kRing < kNK) fr[m % kRing] = load_k(ka, m + kRing);
+            if (m + kRing < kNK) fr[m % kRing] = load_k(ka0, m + kRing);
           }
           settle_s(s);
           const int pos0 = tile_pos(0);
@@ -508,43 +541,95 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           l_run = lsum;
         }
 
-        // ---- tiles 1 .. n-1: S^T of tile `it`, then PV of tile it-1 with the softmax
-        //      arithmetic of tile `it` and the direct loads of tile it+2 spread between
-        //      its MFMAs.  With one wave per SIMD the wave's own instruction issue is the
-        //      scarce resource: everything besides the 68 MFMAs is kept to a minimum. ----
-#pragma unroll 1
-        for (int it = 1; it < n_tiles; ++it) {
-          const int stage = it & (kStages - 1);
-          const uint32_t st = lds0 + stage * kStageBytes;
-          const uint32_t st_prev = lds0 + ((it - 1) & (kStages - 1)) * kStageBytes;
+        // ---- tiles 1 .. n-1 and the last PV as one continuous stream of MFMAs ----
+        // Iteration `it` issues 68 MFMAs: S^T of tile `it` (36), then PV of tile it-1 (32),
+        // with the softmax arithmetic of tile `it` and the direct loads of tile it+2 spread
+        // between them.  With one wave per SIMD the wave's own instruction issue is the
+        // scarce resource, and the matrix pipeline drains whenever the wave does anything
+        // else for long.  So nothing is done between iterations: the operand ring is
+        // continuous across them (fragment m lives in slot m % 8; the next iteration's first
+        // eight fragments are requested behind MFMAs 63 .. 67 as their slots fall free: 4 .. 7
+        // first, then 0 .. 3), the LDS addresses of the next iteration are formed a few at a
+        // time behind MFMAs whose own addresses are no longer needed, and the barrier that
+        // publishes tile it+1 sits behind MFMA 63, where the four fragments still in flight
+        // were requested four MFMAs earlier.
+        KAddr ka;  // K fragments of tile `it` (in use behind MFMAs 60 of the iteration before .. 27)
+        VAddr va;  // V fragments of tile it-1 (in use behind MFMAs 20 .. 59)
+        // table entry of tile it+2: requested behind MFMA 56 of the previous iteration, moved to
+        // scalar registers behind MFMA 66, when it has long arrived
+        u32x2 e_tab;
+        uint32_t e_lo, e_hi;
+        launder_offsets();
+        if (n_tiles > 1) {
           wait_tile();
-          __syncthreads();  // tile `it` is visible; every wave is done with the stage tile it+2 goes to
-          launder_offsets();
-          const KAddr ka = k_addr(st);
-          const VAddr va = v_addr(st_prev);
-          auto frag = [&](int m) -> bf16x8 { return m < kNK ? load_k(ka, m) : load_v(va, m - kNK); };
+          __syncthreads();  // tile 1 is visible
+          ka = k_addr(lds0 + kStageBytes);
 #pragma unroll
-          for (int d = 0; d < kRing; ++d) fr[d] = frag(d);
-          const TileSrc ts = prep_tile(it + 2);
-          const bool full = *LDS_PTR(uint32_t, lds_tiles + it * 8) & 1;
-          bf16x8 pn[2];
+          for (int d = 0; d < kRing; ++d) fr[d] = load_k(ka, d);
+        }
+        e_tab = tile_entry(3);
+        e_lo = __builtin_amdgcn_readfirstlane(e_tab.x);
+        e_hi = __builtin_amdgcn_readfirstlane(e_tab.y);
+
+        auto body = [&](const int it) {
+          const int stage = it & (kStages - 1);
+          const uint32_t st_prev = lds0 + ((it - 1) & (kStages - 1)) * kStageBytes;
+          const uint32_t st_next = lds0 + ((it + 1) & (kStages - 1)) * kStageBytes;
+          const TileSrc ts = prep_tile_e(it + 2, e_lo, e_hi);
+          uint32_t full_word = 1;
           float lsum = 0.f, mt = -INFINITY;
-          // one MFMA and what is issued behind it; M is a compile-time constant
+          bf16x8 pn[2];
+          // One MFMA and what is issued behind it; m is a compile-time constant.
           auto step = [&](auto m_tag) {
             constexpr int m = decltype(m_tag)::value;
-            if constexpr (m == 0) mfma_s_first(s, fr[m % kRing], qf[m]);
-            else if constexpr (m < kNK) mfma_s(s, fr[m % kRing], qf[m]);
-            else mfma_o(acc[(m - kNK) & 15], fr[m % kRing], pf[(m - kNK) >> 4]);
-            if constexpr (m + kRing < kNK + kNV) fr[m % kRing] = frag(m + kRing);
-            // the direct loads of tile it+2, spread evenly over the MFMAs (at most one per MFMA)
-            constexpr int k0 = (m * kDmaPerTile) / (kNK + kNV), k1 = ((m + 1) * kDmaPerTile) / (kNK + kNV);
-            if constexpr (k1 > k0) dma_piece(ts, std::integral_constant<int, k0>{});
+            constexpr int slot = m % kRing;
+            if constexpr (m == 0) mfma_s_first(s, fr[slot], qf[m]);
+            else if constexpr (m < kNK) mfma_s(s, fr[slot], qf[m]);
+            else mfma_o(acc[(m - kNK) & 15], fr[slot], pf[(m - kNK) >> 4]);
+            // the fragment eight MFMAs ahead: of this iteration, or (behind MFMAs 64 .. 67)
+            // K fragments 0 .. 3 of tile it+1.  (After the last tile these read a stage that
+            // holds nothing new; the values are never used.)
+            if constexpr (m + kRing < kNK) fr[slot] = load_k(ka, m + kRing);
+            else if constexpr (m + kRing < kNK + kNV) fr[slot] = load_v(va, m + kRing - kNK);
+            else if constexpr (m >= 64) fr[slot] = load_k(ka, slot);
+            if constexpr (m == 30) full_word = *LDS_PTR(uint32_t, lds_tiles + it * 8);
+            if constexpr (m == 56) e_tab = tile_entry(it + 3);
+            if constexpr (m == 66) {
+              e_lo = __builtin_amdgcn_readfirstlane(e_tab.x);
+              e_hi = __builtin_amdgcn_readfirstlane(e_tab.y);
+            }
+            // the direct loads of tile it+2: one every six MFMAs, all issued by MFMA 51
+            if constexpr (m % 6 == 3 && m / 6 < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m / 6>{});
+            // LDS addresses, formed in registers whose previous contents are no longer needed:
+            // V of tile it-1 behind MFMAs 20 .. 27 (K addresses 0 .. 3 are done with), the
+            // next iteration's K behind MFMAs 60 .. 62
+            if constexpr (m == 20) launder_offsets();
+            if constexpr (m >= 20 && m < 24) va.a[m - 20] = (vb0 ^ ((m - 20) << 6)) + st_prev;
+            if constexpr (m >= 24 && m < 28) va.a[m - 20] = (vb1 ^ ((m - 24) << 6)) + st_prev;
+            if constexpr (m == 60) launder_offsets();
+            if constexpr (m >= 60 && m < 63) {
+              constexpr int q = m - 60;
+#pragma unroll
+              for (int b = 0; b < 4; ++b) {
+                if constexpr (q < 2) ka.a[4 * q + b] = (am ^ ((4 * q + b) << 5)) + st_next;
+                else ka.a[8 + b] = (at ^ (b << 5)) + st_next;
+              }
+            }
+            if constexpr (m == 63) {
+              // Tile it+1 becomes visible, and every wave is done with tile it-1 (its last
+              // fragments were requested behind MFMA 59 and the barrier's fence waits for
+              // them), whose stage the direct loads of the next iteration overwrite.
+              wait_tile();
+              __syncthreads();
+#pragma unroll
+              for (int d = 4; d < 8; ++d) fr[d] = load_k(ka, d);
+            }
             constexpr int j = m - kNK;
             if constexpr (j == 0) {
-              if (FP8 || !full) {  // wave-uniform; rare for a bf16 cache
+              if (FP8 || !(full_word & 1)) {  // wave-uniform; rare for a bf16 cache
                 settle_s(s);
                 if constexpr (FP8) scale_logits(s, stage);
-                if (!full) mask_partial(s, tile_pos(it));
+                if (!(full_word & 1)) mask_partial(s, tile_pos(it));
               }
             }
             // S^T may be read by the vector ALU 12 instructions after its last MFMA: the
@@ -570,13 +655,13 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           l_run += lsum;
           pf[0] = pn[0];
           pf[1] = pn[1];
-        }
-
-        // ---- PV of the last tile ----
+        };
+#pragma unroll 1
+        for (int it = 1; it < n_tiles; ++it) body(it);
+        // ---- PV of the last tile (the one place where the ring starts empty) ----
         {
-          const uint32_t st_last = lds0 + ((n_tiles - 1) & (kStages - 1)) * kStageBytes;
           launder_offsets();
-          const VAddr va = v_addr(st_last);
+          va = v_addr(lds0 + ((n_tiles - 1) & (kStages - 1)) * kStageBytes);
 #pragma unroll
           for (int d = 0; d < kRing; ++d) fr[d] = load_v(va, d);
 #pragma unroll

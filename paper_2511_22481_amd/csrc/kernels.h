@@ -16,7 +16,7 @@ struct DecodeParams {
   float* lse;
   void* part_o;     // [n_slots, head_block, 512] in the output type (bf16 or fp32)
   float* part_lse;  // [n_slots, head_block]
-  const int32_t* unit_seg;
+  const UnitHeader* units;
   const Segment* segs;
   int H, max_pages, S, W, head_block, out_fp32, n_units;
   float scale_log2;  // softmax_scale * log2(e)
