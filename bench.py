@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 WORKLOAD = "r1_b64_32k"
+# HBM bytes per launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this file (profiles/decode_kernel_r1_b64_32k_hbm_counters.md), scaled by what the same
+# counters read for a 1 GiB device copy.  To be re-taken whenever the kernel changes.
+MEASURED_TRAFFIC_BYTES = {"r1_b64_32k": 170_635_000 + 35_520_500}
 
 
 def algorithmic_bytes(retained_tokens, batch, heads, kv_dtype):
@@ -68,18 +72,21 @@ def main():
         sets.append(inp)
     inp0 = sets[0]
     fp8 = cfg.kv_dtype == "fp8"
-    plan = oa.omniattn_plan(inp0.seq_lens_host, batch=inp0.batch, num_heads=inp0.heads,
-                            max_pages_per_seq=inp0.max_pages, num_pages=inp0.num_pages,
-                            sink=inp0.sink, window=inp0.window, softmax_scale=inp0.softmax_scale,
-                            kv_dtype=oa.FP8_E4M3 if fp8 else oa.BF16, out_dtype=oa.BF16)
+    # one plan per input set: sets of a mixed-length workload differ in their lengths
+    plans = [oa.omniattn_plan(s.seq_lens_host, batch=s.batch, num_heads=s.heads,
+                              max_pages_per_seq=s.max_pages, num_pages=s.num_pages,
+                              sink=s.sink, window=s.window, softmax_scale=s.softmax_scale,
+                              kv_dtype=oa.FP8_E4M3 if fp8 else oa.BF16, out_dtype=oa.BF16)
+             for s in sets]
+    plan = plans[0]
     out = torch.empty((inp0.batch, inp0.heads, 512), dtype=torch.bfloat16, device=dev)
     lse = torch.empty((inp0.batch, inp0.heads), dtype=torch.float32, device=dev)
-    ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(max(pl.workspace_bytes for pl in plans), 256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step(i):
         s = sets[i % len(sets)]
-        oa.omniattn_decode(plan, s.q, s.kv_cache, s.kv_scales, s.page_table, out, lse, ws, stream)
+        oa.omniattn_decode(plans[i % len(sets)], s.q, s.kv_cache, s.kv_scales, s.page_table, out, lse, ws, stream)
 
     if args.copy_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -126,7 +133,7 @@ def main():
         evs.append(e)
     for i in range(n_ev):
         s = sets[i % len(sets)]
-        oa.omniattn_decode_timed(plan, s.q, s.kv_cache, s.kv_scales, s.page_table, out, lse, ws,
+        oa.omniattn_decode_timed(plans[i % len(sets)], s.q, s.kv_cache, s.kv_scales, s.page_table, out, lse, ws,
                                  stream, evs[3 * i], evs[3 * i + 1], evs[3 * i + 2])
     torch.cuda.synchronize()
     main_tot = comb_tot = 0.0
@@ -141,7 +148,8 @@ def main():
     for e in evs:
         hip.hipEventDestroy(e)
 
-    retained = plan.retained_tokens
+    # per-step averages over the rotated sets (identical for fixed-length workloads)
+    retained = sum(pl.retained_tokens for pl in plans) / len(plans)
     alg_bytes = algorithmic_bytes(retained, inp0.batch, inp0.heads, cfg.kv_dtype)
     value = retained / (ms_per_step * 1e-3)
     kern_ms = main_ms
@@ -179,7 +187,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
             "kernel_ms": kern_ms,
             "combine_ms": combine_ms,
         },
@@ -200,7 +208,7 @@ def main():
                                  s0.window, s0.softmax_scale, kv_dtype=s0.kv_dtype)
             dt += time.perf_counter() - t0
             reps += 1
-        toks = reps * retained
+        toks = reps * plans[0].retained_tokens
         try:
             cores = len(os.sched_getaffinity(0))
         except AttributeError:
