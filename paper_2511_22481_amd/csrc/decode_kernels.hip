@@ -59,7 +59,10 @@ constexpr int kTailRowBytes = 128;
 constexpr int kTailBase = kTile * kMainRowBytes;                      // 32,768
 constexpr int kStageBytes = kTile * (kMainRowBytes + kTailRowBytes);  // 36,864
 constexpr int kStages = 4;
-constexpr int kScaleBytes = kTile * 4;  // per-token fp32 scales of one stage (fp8 cache)
+constexpr int kScaleBytes = 256;  // per-token fp32 scales of one stage (fp8 cache): 32 used, written twice over by a 64-lane direct load
+// fp8 cache: three bf16 stages; the fourth stage's space holds two buffers of raw tile bytes
+constexpr int kRawTileBytes = kTile * kQK;  // 18,432
+static_assert(2 * kRawTileBytes <= kStageBytes, "raw buffers fit the fourth stage");
 constexpr int kTileTabBytes = kMaxSegTiles * 8;  // first global byte of every tile of the segment
 constexpr int kJunkBytes = 4096;  // target of the direct loads issued for tiles that do not exist
 constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16 + kTileTabBytes + kJunkBytes;  // 16: retry flag
@@ -129,6 +132,14 @@ __device__ __forceinline__ void dma16(const uint8_t* base, uint32_t off) {
   const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
   asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(sbase), "n"(IMM) : "m0");
 }
+// 4 bytes per lane: lane l's dword lands at M0 + 4 l.
+__device__ __forceinline__ void dma4(const uint8_t* base, uint32_t off) {
+  const uint64_t b = (uint64_t)(uintptr_t)base;
+  const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+  const uint32_t b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+  const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
+  asm volatile("global_load_lds_dword %0, %1" : : "v"(off), "s"(sbase) : "m0");
+}
 #pragma clang diagnostic pop
 // Wait until at most N of this wave's vector-memory operations are outstanding.
 template <int N>
@@ -169,7 +180,10 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   };
 
   constexpr int kRowsPerWave = kTile / WAVES;                  // 8, 16 or 32
-  constexpr int kDmaPerTile = kRowsPerWave + kRowsPerWave / 8;  // direct loads per wave and tile
+  // direct loads per wave and tile.  bf16: one per row plus one for the rope parts of 8 rows;
+  // fp8: the tile's 18 KB of codes as 18 pieces dealt round-robin (5 per wave, two of them void)
+  // plus one for its 32 scales
+  constexpr int kDmaPerTile = FP8 ? 6 : kRowsPerWave + kRowsPerWave / 8;
 
   // Work groups are dealt to the eight XCDs round-robin.  Consecutive work units (the
   // pieces of one sequence, which read the same Q and neighbouring pages) are mapped to
@@ -209,6 +223,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const int sink_end = p.S < L ? p.S : L;
 
     auto tile_pos = [&](int it) { return tl.logical(sg.tile_lo + it) * kTile; };
+    // ring position of a tile's bf16 stage (three stages when the fourth holds raw fp8 tiles)
+    auto stage_of = [](int it) { return FP8 ? it % 3 : it & (kStages - 1); };
+    const uint32_t lds_rawbuf = lds0 + 3 * kStageBytes;
     auto tile_full = [&](int pos0) {
       return (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L);
     };
@@ -222,17 +239,21 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       const uint8_t* gbase;   // first byte of the tile's rows in the cache (or any valid address)
       uint32_t lmain, ltail;  // LDS destinations of row 0 (main part, tail part)
       uint32_t mstride, tstride;  // 1024 / 128, or 0 for the junk target
+      const float* sgbase;    // fp8: the tile's 32 scales in global memory
+      uint32_t lscale;        // fp8: their LDS slot
     };
     auto prep_tile_e = [&](int it, uint32_t e_lo, uint32_t e_hi) -> TileSrc {
       TileSrc ts;
       ts.gbase = (const uint8_t*)p.q;
       ts.lmain = ts.ltail = lds_junk;
       ts.mstride = ts.tstride = 0;
+      ts.sgbase = nullptr;
+      ts.lscale = lds_junk;
       if (it >= n_tiles) return ts;
       // table entry: first global byte of the tile's rows; bit 0 = every position retained
       const bool full = e_lo & 1;
       const uint8_t* gbase = (const uint8_t*)(uintptr_t)(((uint64_t)e_hi << 32) | (e_lo & ~1u));
-      const int stage = it & (kStages - 1);
+      const int stage = stage_of(it);
       const uint32_t lbase = lds0 + stage * kStageBytes;
       const int row_w0 = wave * kRowsPerWave;
       if constexpr (!FP8) {
@@ -260,8 +281,19 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         // fp8 rows: 36 chunks of 16 codes; every code is widened exactly to bf16 and the
         // token's fp32 scale is kept aside: it multiplies the logit (after QK^T) and the
         // softmax weight (before PV), both in fp32, so dequantisation adds no rounding.
-        const int pos0 = tile_pos(it);
+        // Tiles 0 and 1 are filled here, through registers; from tile 2 on the raw bytes
+        // and the scales come by direct loads two tiles ahead (dma_piece) and are widened
+        // out of LDS while the tile before is being multiplied (convert pass in the loop).
         const float* sbase = p.kv_scales + (gbase - p.kv) / kQK;
+        if (it >= 2) {
+          ts.gbase = gbase;
+          ts.lmain = lds_rawbuf + (it & 1) * kRawTileBytes;
+          ts.mstride = 1024;
+          ts.sgbase = sbase;
+          ts.lscale = lds_scales + (it & 3) * kScaleBytes;  // four slots: tile it-2's was last read two barriers ago
+          return ts;
+        }
+        const int pos0 = tile_pos(it);
         constexpr int n_chunks = kTile * (kQK / 16);  // 1152
 #pragma unroll 1
         for (int ci = tid; ci < n_chunks; ci += WAVES * 64) {
@@ -284,7 +316,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         }
         if (tid < kTile) {
           const bool ok = full || retained(pos0 + tid, L, p.S, p.W);
-          *LDS_PTR(float, lds_scales + stage * kScaleBytes + tid * 4) = ok ? sbase[tid] : 0.f;
+          *LDS_PTR(float, lds_scales + (it & 3) * kScaleBytes + tid * 4) = ok ? sbase[tid] : 0.f;
         }
       }
       return ts;
@@ -300,7 +332,18 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       uint32_t l16 = lane << 4;
       asm volatile("" : "+v"(l16));
       const int row_w0 = wave * kRowsPerWave;
-      if constexpr (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
+      if constexpr (FP8) {
+        if constexpr (k < 5) {  // piece wave + 4 k of the tile's 18 pieces of 1 KB
+          const int c = wave + 4 * k;
+          const bool real = ts.mstride != 0 && c < kRawTileBytes / 1024;
+          dma_set_lds_base(real ? ts.lmain + c * 1024 : lds_junk);
+          dma16<0>(real ? ts.gbase : (const uint8_t*)p.q, (real ? c * 1024 : 0) + l16);
+        } else {  // the 32 scales (128 bytes): lanes 32..63 fetch the same words again
+          const bool real = ts.mstride != 0 && wave == 0;
+          dma_set_lds_base(real ? ts.lscale : lds_junk);
+          dma4(real ? (const uint8_t*)ts.sgbase : (const uint8_t*)p.q, (l16 >> 2) & 127);
+        }
+      } else if constexpr (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
         constexpr int imm = (k & 3) * kMainRowBytes;
         const int row = row_w0 + k;
         if constexpr ((k & 3) == 0) dma_set_lds_base(ts.lmain + row * ts.mstride);
@@ -378,7 +421,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     issue_tile(0);
     issue_tile(1);
 
-    constexpr int kRing = 8;            // LDS fragment requests kept in flight
+    // LDS fragment requests kept in flight (the fp8 kernel needs the registers for the
+    // widening pass and gets by with a shorter ring); must be 8 or 4
+    constexpr int kRing = FP8 ? 4 : 8;
     constexpr int kNK = kQK / 16;       // 36 MFMAs for S^T
     constexpr int kNV = 2 * (kV / 32);  // 32 MFMAs for O^T
 
@@ -455,13 +500,13 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const float c = p.scale_log2;
     const float masked_raw = c < 0.f ? INFINITY : -INFINITY;
     // fp8: the fp32 scale of the token behind element i, and all sixteen applied to S^T
-    auto tok_scale = [&](int stage, int i) -> float {
-      return *LDS_PTR(float, lds_scales + stage * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
+    auto tok_scale = [&](int slot, int i) -> float {
+      return *LDS_PTR(float, lds_scales + slot * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
     };
-    auto scale_logits = [&](f32x16& s, int stage) {
+    auto scale_logits = [&](f32x16& s, int slot) {
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {  // elements 4 q4 .. 4 q4 + 3 are four consecutive tokens
-        const f32x4 sc = *LDS_PTR(f32x4, lds_scales + stage * kScaleBytes + (q4 * 8 + g * 4) * 4);
+        const f32x4 sc = *LDS_PTR(f32x4, lds_scales + slot * kScaleBytes + (q4 * 8 + g * 4) * 4);
 #pragma unroll
         for (int k = 0; k < 4; ++k) s[q4 * 4 + k] *= sc[k];
       }
@@ -561,7 +606,10 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         uint32_t e_lo, e_hi;
         launder_offsets();
         if (n_tiles > 1) {
-          wait_tile();
+          // bf16: tile 1 has arrived.  fp8: tile 1 was stored by this work group itself; the
+          // raw bytes of tile 2, which iteration 1 widens, must have arrived.
+          if constexpr (FP8) wait_vm<0>();
+          else wait_tile();
           __syncthreads();  // tile 1 is visible
           ka = k_addr(lds0 + kStageBytes);
 #pragma unroll
@@ -572,13 +620,70 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         e_hi = __builtin_amdgcn_readfirstlane(e_tab.y);
 
         auto body = [&](const int it) {
-          const int stage = it & (kStages - 1);
-          const uint32_t st_prev = lds0 + ((it - 1) & (kStages - 1)) * kStageBytes;
-          const uint32_t st_next = lds0 + ((it + 1) & (kStages - 1)) * kStageBytes;
+          const int stage = stage_of(it);
+          const uint32_t st_prev = lds0 + stage_of(it - 1) * kStageBytes;
+          const uint32_t st_next = lds0 + stage_of(it + 1) * kStageBytes;
           const TileSrc ts = prep_tile_e(it + 2, e_lo, e_hi);
           uint32_t full_word = 1;
           float lsum = 0.f, mt = -INFINITY;
           bf16x8 pn[2];
+          // fp8: the raw bytes of tile it+1 (arrived and published by the previous iteration's
+          // barrier) are widened to bf16 into that tile's stage while S^T of tile `it` runs.
+          // Thread t handles row t / 8 and the 16-code chunks (t % 8) + 8 j, j = 0 .. 4 (the
+          // row has 36): chunk j is requested behind MFMA 8 + 5 j and stored, as two bf16
+          // chunks, behind MFMA 11 + 5 j.  Rows outside the retained set (partial tiles) are
+          // stored as zeros and their scales are zeroed: their contents are unspecified.
+          [[maybe_unused]] uint32_t cv_src = 0, cv_d0 = 0, cv_d1 = 0, cv_t0 = 0, cv_t1 = 0, cv_t8 = 0;
+          [[maybe_unused]] bool cv_on = false, cv_rowok = true;
+          [[maybe_unused]] u32x4 cv_raw = {0, 0, 0, 0};
+          auto convert_step = [&](auto m_tag) {
+            constexpr int m = decltype(m_tag)::value;
+            if constexpr (m == 6) {
+              cv_on = it + 1 < n_tiles;
+              uint32_t t = tid;
+              asm volatile("" : "+v"(t));
+              const uint32_t row = t >> 3;
+              cv_t8 = t & 7;
+              const uint32_t e_next = *LDS_PTR(uint32_t, lds_tiles + (it + 1) * 8);
+              cv_rowok = (e_next & 1) || retained(tile_pos(it + 1) + (int)row, L, p.S, p.W);
+              cv_src = lds_rawbuf + ((it + 1) & 1) * kRawTileBytes + row * kQK + cv_t8 * 16;
+              const uint32_t o0 = row * kMainRowBytes + (((2 * cv_t8) ^ swz_main(row)) << 4);
+              const uint32_t o1 = kTailBase + row * kTailRowBytes + (((2 * cv_t8) ^ swz_tail(row)) << 4);
+              cv_d0 = st_next + o0;
+              cv_d1 = st_next + (o0 ^ 16);
+              cv_t0 = st_next + o1;
+              cv_t1 = st_next + (o1 ^ 16);
+              if (cv_on && !(e_next & 1) && t < (uint32_t)kTile && !retained(tile_pos(it + 1) + (int)t, L, p.S, p.W))
+                *LDS_PTR(float, lds_scales + ((it + 1) & 3) * kScaleBytes + t * 4) = 0.f;
+            }
+            if constexpr (m >= 8 && m <= 28 && (m - 8) % 5 == 0) {
+              constexpr int j = (m - 8) / 5;
+              if (cv_on && (j < 4 || cv_t8 < 4)) cv_raw = *LDS_PTR(u32x4, cv_src + 128 * j);
+            }
+            if constexpr (m >= 11 && m <= 31 && (m - 11) % 5 == 0) {
+              constexpr int j = (m - 11) / 5;
+              if (cv_on && (j < 4 || cv_t8 < 4)) {
+                uint32_t w[8];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                  const uint32_t code = cv_rowok ? cv_raw[k] : 0u;
+                  f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(code, false);
+                  f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(code, true);
+                  bf16x2 blo = {(__bf16)lo.x, (__bf16)lo.y};
+                  bf16x2 bhi = {(__bf16)hi.x, (__bf16)hi.y};
+                  w[2 * k] = __builtin_bit_cast(uint32_t, blo);
+                  w[2 * k + 1] = __builtin_bit_cast(uint32_t, bhi);
+                }
+                if constexpr (j < 4) {
+                  *LDS_PTR(u32x4, cv_d0 + 256 * j) = u32x4{w[0], w[1], w[2], w[3]};
+                  *LDS_PTR(u32x4, cv_d1 + 256 * j) = u32x4{w[4], w[5], w[6], w[7]};
+                } else {
+                  *LDS_PTR(u32x4, cv_t0) = u32x4{w[0], w[1], w[2], w[3]};
+                  *LDS_PTR(u32x4, cv_t1) = u32x4{w[4], w[5], w[6], w[7]};
+                }
+              }
+            }
+          };
           // One MFMA and what is issued behind it; m is a compile-time constant.
           auto step = [&](auto m_tag) {
             constexpr int m = decltype(m_tag)::value;
@@ -598,8 +703,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               e_lo = __builtin_amdgcn_readfirstlane(e_tab.x);
               e_hi = __builtin_amdgcn_readfirstlane(e_tab.y);
             }
-            // the direct loads of tile it+2: one every six MFMAs, all issued by MFMA 51
-            if constexpr (m % 6 == 3 && m / 6 < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m / 6>{});
+            // the direct loads of tile it+2.  bf16: one every six MFMAs, all issued by MFMA 51.
+            // fp8: behind the first six MFMAs, so that the raw bytes have the whole iteration
+            // to arrive before the barrier behind MFMA 63 hands them to the next iteration.
+            if constexpr (!FP8 && m % 6 == 3 && m / 6 < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m / 6>{});
+            if constexpr (FP8 && m < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m>{});
+            if constexpr (FP8) convert_step(m_tag);
             // LDS addresses, formed in registers whose previous contents are no longer needed:
             // V of tile it-1 behind MFMAs 20 .. 27 (K addresses 0 .. 3 are done with), the
             // next iteration's K behind MFMAs 60 .. 62
@@ -619,16 +728,19 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               // Tile it+1 becomes visible, and every wave is done with tile it-1 (its last
               // fragments were requested behind MFMA 59 and the barrier's fence waits for
               // them), whose stage the direct loads of the next iteration overwrite.
-              wait_tile();
+              if constexpr (FP8) wait_vm<0>();  // the raw bytes of tile it+2 (and tile it+1 is widened)
+              else wait_tile();
               __syncthreads();
+              if constexpr (kRing == 8) {
 #pragma unroll
-              for (int d = 4; d < 8; ++d) fr[d] = load_k(ka, d);
+                for (int d = 4; d < 8; ++d) fr[d] = load_k(ka, d);
+              }
             }
             constexpr int j = m - kNK;
             if constexpr (j == 0) {
               if (FP8 || !(full_word & 1)) {  // wave-uniform; rare for a bf16 cache
                 settle_s(s);
-                if constexpr (FP8) scale_logits(s, stage);
+                if constexpr (FP8) scale_logits(s, it & 3);
                 if (!(full_word & 1)) mask_partial(s, tile_pos(it));
               }
             }
@@ -643,7 +755,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
                 mt = fmaxf(mt, t);
                 float e = __builtin_amdgcn_exp2f(t);
                 lsum += e;
-                if constexpr (FP8) e *= tok_scale(stage, i);
+                if constexpr (FP8) e *= tok_scale(it & 3, i);
                 pn[i >> 3][i & 7] = (__bf16)e;
               }
             }
@@ -661,7 +773,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         // ---- PV of the last tile (the one place where the ring starts empty) ----
         {
           launder_offsets();
-          va = v_addr(lds0 + ((n_tiles - 1) & (kStages - 1)) * kStageBytes);
+          va = v_addr(lds0 + stage_of(n_tiles - 1) * kStageBytes);
 #pragma unroll
           for (int d = 0; d < kRing; ++d) fr[d] = load_v(va, d);
 #pragma unroll
