@@ -223,6 +223,52 @@ def test_fp8_cache(q_std):
     parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what="fp8")
 
 
+def test_many_short_sequences_share_work_units():
+    """bf16 cache, more sequences than compute units: several segments per work unit, with
+    one-tile and two-tile segments among them (the MFMA stream's shortest paths)."""
+    rng = np.random.default_rng(18)
+    lens = [int(x) for x in rng.integers(1, 300, size=700)]
+    inp = parity.to_device(make_custom(700, 48, lens, 16, 96, seed=22, q_std=0.5, kv_std=0.5))
+    out, lse, plan = parity.run_gpu(inp)
+    assert plan.num_segments > plan.num_units
+    parity.assert_parity(inp, out, lse, row_rel_l2=1e-2, what="short sequences")
+
+
+def test_fp8_many_short_sequences_share_work_units():
+    """More sequences than compute units: every work unit runs several segments, so the
+    tile pipeline (direct loads, widening pass, scale slots) restarts inside one launch."""
+    rng = np.random.default_rng(17)
+    lens = [int(x) for x in rng.integers(33, 420, size=600)]
+    inp = parity.to_device(make_custom(600, 16, lens, 32, 200, seed=21, kv_dtype="fp8", q_std=0.3, kv_std=1.0))
+    out, lse, plan = parity.run_gpu(inp)
+    assert plan.num_segments > plan.num_units
+    parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what="fp8 short sequences")
+
+
+def test_fp8_reference_overflow_retry():
+    """The second attempt of a segment (exact softmax reference) with the fp8 tile pipeline."""
+    from workloads.generate import quantize_fp8_per_token
+    L = 640
+    inp = make_custom(2, 32, [L, L], 0, 4096, seed=4, kv_dtype="fp8", q_std=1.0 / 24, kv_std=1.0)
+    inp.q.zero_()
+    inp.q[:, :, 540] = 64.0
+    for b in range(2):
+        rows = torch.zeros(L, 576)
+        j = torch.arange(L)
+        rows[:, 540] = (j // 8).float() / 4.0     # the logit climbs to ~131 in log2 units
+        rows[:, 3] = (j % 5).float()
+        codes, scales = quantize_fp8_per_token(rows)
+        for pg in range((L + PAGE - 1) // PAGE):
+            n = min(PAGE, L - pg * PAGE)
+            phys = int(inp.page_table[b, pg])
+            inp.kv_cache[phys, :n] = codes[pg * PAGE: pg * PAGE + n]
+            inp.kv_scales[phys, :n] = scales[pg * PAGE: pg * PAGE + n]
+    inp = parity.to_device(inp)
+    out, lse, _ = parity.run_gpu(inp, out_dtype=torch.float32)
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+    parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what="fp8 overflow retry")
+
+
 # --------------------------------------------------- full-size workloads, sampled outputs ---
 @pytest.mark.parametrize("name,n_pairs", [("r1_b64_32k", 64), ("dense_b32_4k", 48), ("fp8_b32_128k", 32),
                                           ("mixed_b256", 64)])
