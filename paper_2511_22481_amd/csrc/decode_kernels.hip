@@ -4,7 +4,8 @@
 // Main kernel: one work group per work unit, WAVES waves, one wave per SIMD; each
 // wave owns 32 heads and the full 512-wide output row of those heads.
 //   a3  retained 32-token tiles stream into a ring of four LDS stages by direct
-//       global->LDS 16-byte loads, two tiles ahead of the compute;
+//       global->LDS 16-byte loads, two tiles ahead of the compute (fp8 cache: the
+//       raw bytes come the same way and are widened to bf16 out of LDS);
 //   a4  S^T[token, head] = K_tile . Q^T on 32x32x16 bf16 MFMA, Q held in
 //       registers as the B operand for the whole segment;
 //   a5  positions outside the retained set get -inf (partial tiles only);
@@ -14,8 +15,8 @@
 //       exactly the B layout P^T needs, so P never leaves registers; V^T comes
 //       from the same LDS tile through transposing LDS reads.  The PV MFMAs of
 //       tile i-1 are issued interleaved with the softmax arithmetic of tile i;
-//   a8  normalise, transpose through LDS, write bf16/fp32 rows + lse, or an fp32
-//       partial row.
+//   a8  normalise, transpose through LDS, write bf16/fp32 rows + lse to the output
+//       or, for a split sequence, to a partial slot (same type).
 // Combine kernel (a9): merges the partials of sequences that were split.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -536,9 +537,10 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       float mt_all = -INFINITY;  // running maximum of this lane's t = s * c - ref
 
       if (n_tiles > 0) {
-        // pf: bf16 weights of the previous tile (B operand of PV); fr: the ring of operand
-        // fragments requested ahead.
-        bf16x8 pf[2], fr[kRing];
+        // pn: bf16 weights of the tile whose S^T was computed last (the loop copies them to the
+        // B operand registers of its PV MFMAs early in the next iteration); fr: the ring of
+        // operand fragments requested ahead.
+        bf16x8 pn[2], fr[kRing];
         f32x16 s;
 
         // ---- tile 0: S^T, reference, weights (no PV to overlap with yet) ----
@@ -581,7 +583,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             float e = __builtin_amdgcn_exp2f(t);
             lsum += e;
             if constexpr (FP8) e *= tok_scale(0, i);
-            pf[i >> 3][i & 7] = (__bf16)e;
+            pn[i >> 3][i & 7] = (__bf16)e;
           }
           l_run = lsum;
         }
@@ -600,8 +602,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         // were requested four MFMAs earlier.
         KAddr ka;  // K fragments of tile `it` (in use behind MFMAs 60 of the iteration before .. 27)
         VAddr va;  // V fragments of tile it-1 (in use behind MFMAs 20 .. 59)
-        // table entry of tile it+2: requested behind MFMA 56 of the previous iteration, moved to
-        // scalar registers behind MFMA 66, when it has long arrived
+        // table entry of tile it+2: requested behind MFMA 16 of the previous iteration, moved to
+        // scalar registers behind MFMA 34, when it has long arrived
         u32x2 e_tab;
         uint32_t e_lo, e_hi;
         launder_offsets();
@@ -626,7 +628,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           const TileSrc ts = prep_tile_e(it + 2, e_lo, e_hi);
           uint32_t full_word = 1;
           float lsum = 0.f, mt = -INFINITY;
-          bf16x8 pn[2];
+          bf16x8 pf[2];  // weights of tile it-1, taken over from pn behind MFMA 2
           // fp8: the raw bytes of tile it+1 (arrived and published by the previous iteration's
           // barrier) are widened to bf16 into that tile's stage while S^T of tile `it` runs.
           // Thread t handles row t / 8 and the 16-code chunks (t % 8) + 8 j, j = 0 .. 4 (the
@@ -697,16 +699,22 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             if constexpr (m + kRing < kNK) fr[slot] = load_k(ka, m + kRing);
             else if constexpr (m + kRing < kNK + kNV) fr[slot] = load_v(va, m + kRing - kNK);
             else if constexpr (m >= 64) fr[slot] = load_k(ka, slot);
+            if constexpr (m == 2) {
+              pf[0] = pn[0];
+              pf[1] = pn[1];
+            }
             if constexpr (m == 30) full_word = *LDS_PTR(uint32_t, lds_tiles + it * 8);
-            if constexpr (m == 56) e_tab = tile_entry(it + 3);
-            if constexpr (m == 66) {
+            if constexpr (m == 16) e_tab = tile_entry(it + 3);
+            if constexpr (m == 34) {
               e_lo = __builtin_amdgcn_readfirstlane(e_tab.x);
               e_hi = __builtin_amdgcn_readfirstlane(e_tab.y);
             }
-            // the direct loads of tile it+2.  bf16: one every six MFMAs, all issued by MFMA 51.
+            // the direct loads of tile it+2.  bf16: one every four MFMAs of the S^T phase (whose
+            // MFMAs leave issue slots free; the PV phase, with two LDS reads and a softmax element
+            // per MFMA, has none to spare).
             // fp8: behind the first six MFMAs, so that the raw bytes have the whole iteration
             // to arrive before the barrier behind MFMA 63 hands them to the next iteration.
-            if constexpr (!FP8 && m % 6 == 3 && m / 6 < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m / 6>{});
+            if constexpr (!FP8 && m % 4 == 1 && m / 4 < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m / 4>{});
             if constexpr (FP8 && m < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m>{});
             if constexpr (FP8) convert_step(m_tag);
             // LDS addresses, formed in registers whose previous contents are no longer needed:
@@ -765,8 +773,6 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           }(std::make_integer_sequence<int, kNK + kNV>{});
           mt_all = fmaxf(mt_all, mt);
           l_run += lsum;
-          pf[0] = pn[0];
-          pf[1] = pn[1];
         };
 #pragma unroll 1
         for (int it = 1; it < n_tiles; ++it) body(it);
@@ -778,7 +784,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           for (int d = 0; d < kRing; ++d) fr[d] = load_v(va, d);
 #pragma unroll
           for (int j = 0; j < kNV; ++j) {
-            mfma_o(acc[j & 15], fr[j % kRing], pf[j >> 4]);
+            mfma_o(acc[j & 15], fr[j % kRing], pn[j >> 4]);
             if (j + kRing < kNV) fr[j % kRing] = load_v(va, j + kRing);
           }
           settle_o(acc);  // the compiler may move the tile between registers right after this
