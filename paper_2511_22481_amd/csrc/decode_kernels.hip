@@ -225,7 +225,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 
     auto tile_pos = [&](int it) { return tl.logical(sg.tile_lo + it) * kTile; };
     // ring position of a tile's bf16 stage (three stages when the fourth holds raw fp8 tiles)
-    auto stage_of = [](int it) { return FP8 ? it % 3 : it & (kStages - 1); };
+    // (unsigned: a signed remainder could be negative as far as the compiler knows, and it
+    // then refuses to fold constant offsets into the LDS instructions built on these addresses)
+    auto stage_of = [](int it) -> uint32_t { return FP8 ? (uint32_t)it % 3u : (uint32_t)it & (kStages - 1); };
     const uint32_t lds_rawbuf = lds0 + 3 * kStageBytes;
     auto tile_full = [&](int pos0) {
       return (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L);
@@ -501,13 +503,20 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const float c = p.scale_log2;
     const float masked_raw = c < 0.f ? INFINITY : -INFINITY;
     // fp8: the fp32 scale of the token behind element i, and all sixteen applied to S^T
-    auto tok_scale = [&](int slot, int i) -> float {
-      return *LDS_PTR(float, lds_scales + slot * kScaleBytes + ((i >> 2) * 8 + g * 4 + (i & 3)) * 4);
+    // Elements 4 q .. 4 q + 3 of a lane are four consecutive tokens (8 q + 4 g ..): their
+    // scales are one 16-byte LDS read at a lane base plus a constant.  The base goes through
+    // an opaque move, or the compiler keeps one address register per element alive.
+    auto scale_base = [&](int slot) -> uint32_t {
+      uint32_t b = lds_scales + slot * kScaleBytes + g * 16;
+      asm volatile("" : "+v"(b));
+      return b;
     };
+    auto tok_scale4 = [&](uint32_t base, int q) -> f32x4 { return *LDS_PTR(f32x4, base + q * 32); };
     auto scale_logits = [&](f32x16& s, int slot) {
+      const uint32_t base = scale_base(slot);
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {  // elements 4 q4 .. 4 q4 + 3 are four consecutive tokens
-        const f32x4 sc = *LDS_PTR(f32x4, lds_scales + slot * kScaleBytes + (q4 * 8 + g * 4) * 4);
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 sc = tok_scale4(base, q4);
 #pragma unroll
         for (int k = 0; k < 4; ++k) s[q4 * 4 + k] *= sc[k];
       }
@@ -576,13 +585,19 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             ref = m2 == -INFINITY ? 0.f : ceilf(m2);
           }
           float lsum = 0.f;
+          [[maybe_unused]] uint32_t sc_base = 0;
+          [[maybe_unused]] f32x4 sc4 = {0.f, 0.f, 0.f, 0.f};
+          if constexpr (FP8) sc_base = scale_base(0);
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const float t = fmaf(s[i], c, -ref);
             mt_all = fmaxf(mt_all, t);
             float e = __builtin_amdgcn_exp2f(t);
             lsum += e;
-            if constexpr (FP8) e *= tok_scale(0, i);
+            if constexpr (FP8) {
+              if ((i & 3) == 0) sc4 = tok_scale4(sc_base, i >> 2);
+              e *= sc4[i & 3];
+            }
             pn[i >> 3][i & 7] = (__bf16)e;
           }
           l_run = lsum;
@@ -628,6 +643,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           const TileSrc ts = prep_tile_e(it + 2, e_lo, e_hi);
           uint32_t full_word = 1;
           float lsum = 0.f, mt = -INFINITY;
+          [[maybe_unused]] uint32_t sc_base = 0;
+          [[maybe_unused]] f32x4 sc4 = {0.f, 0.f, 0.f, 0.f};
           bf16x8 pf[2];  // weights of tile it-1, taken over from pn behind MFMA 2
           // fp8: the raw bytes of tile it+1 (arrived and published by the previous iteration's
           // barrier) are widened to bf16 into that tile's stage while S^T of tile `it` runs.
@@ -723,6 +740,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             if constexpr (m == 20) launder_offsets();
             if constexpr (m >= 20 && m < 24) va.a[m - 20] = (vb0 ^ ((m - 20) << 6)) + st_prev;
             if constexpr (m >= 24 && m < 28) va.a[m - 20] = (vb1 ^ ((m - 24) << 6)) + st_prev;
+            // (opaque: otherwise the compiler may rebase these addresses on one another and pay
+            // for it with an add in front of every LDS read instead of using the offset field)
+            if constexpr (m >= 20 && m < 28) asm volatile("" : "+v"(va.a[m - 20]));
             if constexpr (m == 60) launder_offsets();
             if constexpr (m >= 60 && m < 63) {
               constexpr int q = m - 60;
@@ -730,6 +750,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               for (int b = 0; b < 4; ++b) {
                 if constexpr (q < 2) ka.a[4 * q + b] = (am ^ ((4 * q + b) << 5)) + st_next;
                 else ka.a[8 + b] = (at ^ (b << 5)) + st_next;
+                asm volatile("" : "+v"(ka.a[q < 2 ? 4 * q + b : 8 + b]));
               }
             }
             if constexpr (m == 63) {
@@ -763,7 +784,11 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
                 mt = fmaxf(mt, t);
                 float e = __builtin_amdgcn_exp2f(t);
                 lsum += e;
-                if constexpr (FP8) e *= tok_scale(it & 3, i);
+                if constexpr (FP8) {
+                  if constexpr (i == 0) sc_base = scale_base(it & 3);
+                  if constexpr ((i & 3) == 0) sc4 = tok_scale4(sc_base, i >> 2);
+                  e *= sc4[i & 3];
+                }
                 pn[i >> 3][i & 7] = (__bf16)e;
               }
             }
