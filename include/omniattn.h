@@ -161,6 +161,41 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
                           float* lse, void* workspace, size_t workspace_bytes, void* hip_stream,
                           void* ev_begin, void* ev_main_end, void* ev_end);
 
+/*
+ * Physically compressed cache of a compressed layer.  Section 3.2.1 keeps only the
+ * N_sink first and the N_recent last tokens of a sequence, so such a layer never has
+ * to store more: a sequence owns omniattn_ring_pages(S, W) pages however long it
+ * grows - ceil(S/128) pinned pages for the logical pages that hold sink tokens, and
+ * a ring of ceil(W/128) + 1 pages which all later logical pages use in turn.  A ring
+ * page is handed to a new logical page only when every token of its previous
+ * logical page has left the window (see omniattn_ring_slot).  The decode entry
+ * points need nothing new: the page table simply maps the retained logical pages to
+ * these pages, and entries of logical pages that hold no retained token are never
+ * read.
+ *
+ * omniattn_ring_slot   which of the sequence's own pages (0 .. ring_pages-1) holds
+ *                      logical page `logical_page` (host, pure function; negative
+ *                      arguments give -1).
+ * omniattn_ring_append appends one token to every sequence of the batch (device
+ *                      work on `hip_stream`, asynchronous, allocates nothing):
+ *   prob       batch, max_pages_per_seq, sink, window, kv_dtype are used
+ *   seq_lens   device int32 [B]: lengths before the call; each is incremented
+ *   new_rows   device [B, 576] bf16, or e4m3 bytes for an fp8 cache
+ *   new_scales device fp32 [B] for an fp8 cache, else NULL
+ *   seq_pages  device int32 [B, omniattn_ring_pages(S, W)]: the pool pages each
+ *              sequence owns (distinct)
+ *   kv_cache, kv_scales  the pool, as for omniattn_decode
+ *   page_table device int32 [B, max_pages_per_seq]: entry L/128 of row b is written
+ *              when the new token (position L) opens a logical page
+ * A sequence whose length has reached 128 * max_pages_per_seq is left unchanged
+ * (nothing written, length not incremented); the caller can see that from seq_lens.
+ */
+int32_t omniattn_ring_pages(int32_t sink, int32_t window);
+int32_t omniattn_ring_slot(int32_t sink, int32_t window, int32_t logical_page);
+int omniattn_ring_append(const omniattn_problem_t* prob, int32_t* seq_lens, const void* new_rows,
+                         const float* new_scales, const int32_t* seq_pages, void* kv_cache,
+                         float* kv_scales, int32_t* page_table, void* hip_stream);
+
 const char* omniattn_strerror(int code);
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char* omniattn_last_hip_error(void);

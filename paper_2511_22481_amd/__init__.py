@@ -12,6 +12,9 @@ from .binding import (  # noqa: F401
     omniattn_plan_host,
     omniattn_decode,
     omniattn_decode_timed,
+    omniattn_ring_pages,
+    omniattn_ring_slot,
+    omniattn_ring_append,
     decode,
     lib_path,
     load_library,

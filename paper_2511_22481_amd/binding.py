@@ -69,6 +69,12 @@ def load_library():
     lib.omniattn_decode.argtypes = [P, P, P, P, P, P, P, P, ctypes.c_size_t, P]
     lib.omniattn_decode_timed.restype = ctypes.c_int
     lib.omniattn_decode_timed.argtypes = [P, P, P, P, P, P, P, P, ctypes.c_size_t, P, P, P, P]
+    lib.omniattn_ring_pages.restype = ctypes.c_int32
+    lib.omniattn_ring_pages.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.omniattn_ring_slot.restype = ctypes.c_int32
+    lib.omniattn_ring_slot.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+    lib.omniattn_ring_append.restype = ctypes.c_int
+    lib.omniattn_ring_append.argtypes = [ctypes.POINTER(Problem), P, P, P, P, P, P, P, P]
     lib.omniattn_strerror.restype = ctypes.c_char_p
     lib.omniattn_strerror.argtypes = [ctypes.c_int]
     lib.omniattn_last_hip_error.restype = ctypes.c_char_p
@@ -187,6 +193,32 @@ def omniattn_decode_timed(plan, q, kv_cache, kv_scales, page_table, out, lse, wo
         plan.handle, _ptr(q), _ptr(kv_cache), _ptr(kv_scales), _ptr(page_table), _ptr(out),
         _ptr(lse), _ptr(workspace), ws_bytes, ctypes.c_void_p(stream.cuda_stream),
         ev_begin, ev_main_end, ev_end))
+
+
+def omniattn_ring_pages(sink, window):
+    """Pages a sequence of a compressed layer owns."""
+    return int(load_library().omniattn_ring_pages(sink, window))
+
+
+def omniattn_ring_slot(sink, window, logical_page):
+    """Which of the sequence's own pages holds logical page `logical_page`."""
+    return int(load_library().omniattn_ring_slot(sink, window, logical_page))
+
+
+def omniattn_ring_append(seq_lens, new_rows, new_scales, seq_pages, kv_cache, kv_scales, page_table,
+                         *, sink, window, stream=None):
+    """Append one token per sequence to a physically compressed cache (all CUDA tensors,
+    seq_lens int32 [B] is incremented in place)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    fp8 = kv_cache.dtype == torch.float8_e4m3fn
+    prob = _problem(batch=int(seq_lens.shape[0]), num_heads=1, max_pages_per_seq=int(page_table.shape[1]),
+                    num_pages=int(kv_cache.shape[0]), sink=sink, window=window, softmax_scale=1.0,
+                    kv_dtype=FP8_E4M3 if fp8 else BF16)
+    _check(load_library().omniattn_ring_append(
+        ctypes.byref(prob), _ptr(seq_lens), _ptr(new_rows), _ptr(new_scales), _ptr(seq_pages),
+        _ptr(kv_cache), _ptr(kv_scales), _ptr(page_table), ctypes.c_void_p(stream.cuda_stream)))
 
 
 def decode(q, kv_cache, kv_scales, page_table, seq_lens_host, sink, window, softmax_scale,

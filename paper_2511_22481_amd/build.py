@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libomniattn.so")
-SOURCES = ["decode_kernels.hip", "api.cpp", "plan.cpp"]
+SOURCES = ["decode_kernels.hip", "append_kernels.hip", "api.cpp", "plan.cpp"]
 HEADERS = ["kernels.h", "plan.h", os.path.join("..", "..", "include", "omniattn.h")]
 
 

@@ -234,6 +234,44 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   return OMNIATTN_OK;
 }
 
+int32_t omniattn_ring_pages(int32_t sink, int32_t window) {
+  if (sink < 0 || window < 0) return -1;
+  return ring_pinned_pages(sink) + ring_ring_pages(window);
+}
+
+int32_t omniattn_ring_slot(int32_t sink, int32_t window, int32_t logical_page) {
+  if (sink < 0 || window < 0 || logical_page < 0) return -1;
+  return ring_slot(sink, window, logical_page);
+}
+
+int omniattn_ring_append(const omniattn_problem_t* prob, int32_t* seq_lens, const void* new_rows,
+                         const float* new_scales, const int32_t* seq_pages, void* kv_cache,
+                         float* kv_scales, int32_t* page_table, void* hip_stream) {
+  if (!prob || !seq_lens || !new_rows || !seq_pages || !kv_cache || !page_table) return OMNIATTN_EINVAL;
+  if (prob->batch < 1 || prob->max_pages_per_seq < 1 || prob->sink < 0 || prob->window < 0)
+    return OMNIATTN_EINVAL;
+  if (prob->qk_dim != kQK || prob->page_size != kPage) return OMNIATTN_EUNSUPPORTED;
+  const bool fp8 = prob->kv_dtype == OMNIATTN_FP8_E4M3;
+  if (!fp8 && prob->kv_dtype != OMNIATTN_BF16) return OMNIATTN_EUNSUPPORTED;
+  if (fp8 && (!new_scales || !kv_scales)) return OMNIATTN_EINVAL;
+  if ((((uintptr_t)new_rows | (uintptr_t)kv_cache) & 15) != 0) return OMNIATTN_EINVAL;
+  AppendParams ap;
+  ap.seq_lens = seq_lens;
+  ap.new_rows = (const uint8_t*)new_rows;
+  ap.new_scales = fp8 ? new_scales : nullptr;
+  ap.seq_pages = seq_pages;
+  ap.kv = (uint8_t*)kv_cache;
+  ap.kv_scales = kv_scales;
+  ap.page_table = page_table;
+  ap.max_pages = prob->max_pages_per_seq;
+  ap.S = prob->sink;
+  ap.W = prob->window;
+  ap.ring_pages = ring_pinned_pages(prob->sink) + ring_ring_pages(prob->window);
+  ap.row_bytes = fp8 ? kQK : kQK * 2;
+  OA_HIP(launch_append(ap, prob->batch, (hipStream_t)hip_stream));
+  return OMNIATTN_OK;
+}
+
 const char* omniattn_strerror(int code) {
   switch (code) {
     case OMNIATTN_OK: return "ok";

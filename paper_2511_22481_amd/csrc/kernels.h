@@ -31,6 +31,18 @@ struct CombineParams {
   int H, head_block, out_fp32;
 };
 
+struct AppendParams {
+  int32_t* seq_lens;
+  const uint8_t* new_rows;
+  const float* new_scales;
+  const int32_t* seq_pages;
+  uint8_t* kv;
+  float* kv_scales;
+  int32_t* page_table;
+  int max_pages, S, W, ring_pages, row_bytes;  // row_bytes: 1152 (bf16) or 576 (fp8)
+};
+hipError_t launch_append(const AppendParams& p, int batch, hipStream_t stream);
+
 // One-time per-process kernel attribute setup (large dynamic LDS).
 hipError_t init_kernels();
 // waves must be 4; grid = number of work units.

@@ -52,6 +52,18 @@ OA_HD inline TileLayout tile_layout(int L, int S, int W) {
   return t;
 }
 
+// Physically compressed cache: pages a sequence owns, and which of them holds a logical page.
+// The first ceil(S/page) logical pages (those with sink tokens) are pinned; later logical pages
+// share a ring of ceil(W/page) + 1 pages.  When logical page lp + ring opens (token position
+// (lp + ring) * page), the newest token of logical page lp is ring * page - 127 >= W + 2
+// positions back, outside the window, and it is no sink page: its page may be reused.
+OA_HD inline int ring_pinned_pages(int S) { return S > 0 ? (S + kPage - 1) / kPage : 0; }
+OA_HD inline int ring_ring_pages(int W) { return (W > 0 ? (W + kPage - 1) / kPage : 0) + 1; }
+OA_HD inline int ring_slot(int S, int W, int lp) {
+  const int ps = ring_pinned_pages(S);
+  return lp < ps ? lp : ps + (lp - ps) % ring_ring_pages(W);
+}
+
 // One contiguous run of retained tiles of one (sequence, head block), processed
 // by one work unit.  Layout is part of the ABI (omniattn_plan_get_segments).
 struct Segment {
