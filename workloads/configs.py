@@ -49,6 +49,10 @@ CONFIGS = {
     # every position retained: must equal dense attention
     "dense_b32_4k": Config("dense_b32_4k", batch=32, heads=128, sink=128, window=8192,
                            ctx=4096, seed=20251125),
+    # the headline shape with nothing compressed (a layer the pattern search leaves dense):
+    # every one of the 32768 positions is retained
+    "r1_b64_32k_dense": Config("r1_b64_32k_dense", batch=64, heads=128, sink=0, window=32768,
+                               ctx=32768, seed=20251127),
     # long context, fp8 e4m3 cache with one fp32 scale per token
     "fp8_b32_128k": Config("fp8_b32_128k", batch=32, heads=128, sink=128, window=8192,
                            ctx=131072, kv_dtype="fp8", kv_std=1.0, seed=20251126),
