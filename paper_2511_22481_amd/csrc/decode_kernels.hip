@@ -131,7 +131,9 @@ __device__ __forceinline__ void dma16(const uint8_t* base, uint32_t off) {
   const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
   const uint32_t b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
   const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
-  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(sbase), "n"(IMM) : "m0");
+  // nt: cache rows are read once per work unit; marking them as streaming keeps them from
+  // pushing Q (shared by the units of a sequence) and the partial results out of the caches
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2 nt" : : "v"(off), "s"(sbase), "n"(IMM) : "m0");
 }
 // 4 bytes per lane: lane l's dword lands at M0 + 4 l.
 __device__ __forceinline__ void dma4(const uint8_t* base, uint32_t off) {
