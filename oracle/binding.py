@@ -45,7 +45,7 @@ def _bind(lib):
         ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
         ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
         ctypes.c_double, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
-        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32]
     lib.oracle_bf16_to_double.restype = ctypes.c_double
     lib.oracle_bf16_to_double.argtypes = [ctypes.c_uint16]
     lib.oracle_fp8_e4m3_to_double.restype = ctypes.c_double
@@ -84,12 +84,14 @@ def _raw(t, np_dtype):
 
 def oracle_decode(q, kv_cache, kv_scales, page_table, seq_lens, sink, window,
                   softmax_scale, *, kv_dtype="bf16", pairs=None, want_probs=False,
-                  lib=None):
+                  lib=None, q_len=1):
     """Run the oracle.
 
     q [B,H,576] bf16; kv_cache [P,128,576] bf16 or float8_e4m3fn; kv_scales
     [P,128] fp32 or None; page_table [B,max_pages] int32; seq_lens [B].
     `pairs` = optional int array [n,2] of (b, h) to evaluate (default: all).
+    q_len > 1: q is [B, q_len*H', 576] (query-major), the queries are the last q_len
+    tokens of each sequence and attend causally.
     The scale is first rounded to fp32, the type the decode library receives.
     Returns (out float64 [B,H,512] or [n,512], lse float64 [B,H] or [n])
     and, with want_probs, the softmax weights [.., max_L].
@@ -127,7 +129,7 @@ def oracle_decode(q, kv_cache, kv_scales, page_table, seq_lens, sink, window,
 
     rc = L.omniattn_oracle(B, H, p(qa), p(ca), code, p(sa), num_pages, p(pt), max_pages,
                            p(sl), int(sink), int(window), float(np.float32(softmax_scale)), p(pa), n,
-                           p(out), p(lse), p(probs), max_L)
+                           p(out), p(lse), p(probs), max_L, int(q_len))
     if rc != 0:
         raise RuntimeError(f"oracle failed with code {rc}")
     if pairs is None:

@@ -83,6 +83,13 @@ int oracle_is_retained(int64_t j, int64_t L, int64_t S, int64_t W)
  * Compute out/lse for n_pairs (b, h) pairs.  pairs == NULL means every pair
  * of the B x H grid in row-major order (then n_pairs must equal B*H).
  *
+ * Several queries per sequence (the first equation of section 3.2.1 has a
+ * query matrix of K rows): q_len >= 1 consecutive tokens, the last q_len of
+ * the sequence, each attend causally.  The H rows of a sequence are then
+ * q_len groups of H / q_len heads, group t belonging to the query at position
+ * L - q_len + t, which sees the keys 0 .. L - q_len + t, i.e. a sequence of
+ * length L - (q_len - 1 - t) to which the retained-set rule is applied as is.
+ *
  *   q          bf16 bits  [B, H, 576]
  *   cache      bf16 bits or e4m3 bytes [num_pages, 128, 576]
  *   scales     fp32 [num_pages, 128], used only for e4m3
@@ -99,9 +106,11 @@ int omniattn_oracle(int32_t B, int32_t H, const uint16_t *q, const void *cache,
                     const int32_t *page_table, int32_t max_pages,
                     const int32_t *seq_lens, int32_t S, int32_t W, double scale,
                     const int32_t *pairs, int64_t n_pairs, double *out,
-                    double *lse, double *probs, int64_t max_L)
+                    double *lse, double *probs, int64_t max_L, int32_t q_len)
 {
     if (B < 0 || H < 0 || S < 0 || W < 0 || !out || !lse)
+        return -1;
+    if (q_len < 1 || H % q_len != 0)
         return -1;
     if (!pairs && n_pairs != (int64_t)B * H)
         return -1;
@@ -113,7 +122,12 @@ int omniattn_oracle(int32_t B, int32_t H, const uint16_t *q, const void *cache,
     for (int64_t i = 0; i < n_pairs; ++i) {
         int32_t b = pairs ? pairs[2 * i] : (int32_t)(i / H);
         int32_t h = pairs ? pairs[2 * i + 1] : (int32_t)(i % H);
-        int64_t L = seq_lens[b];
+        int64_t L_seq = seq_lens[b];
+        int32_t Hq = H / q_len;                /* heads per query */
+        int32_t t = h / Hq;                    /* which of the q_len queries this row is */
+        int64_t L = L_seq - (q_len - 1 - t);   /* the keys this query sees: 0 .. L-1 */
+        if (L < 0)
+            L = 0;
         double *o = out + i * V_DIM;
         for (int c = 0; c < V_DIM; ++c)
             o[c] = 0.0;

@@ -370,6 +370,29 @@ def pin_scale_and_value_slice(lib=None):
     assert out.shape[-1] == DV
 
 
+def pin_multi_query(lib=None):
+    """Several causal queries per sequence: the rows of query t must equal plain library
+    attention over the explicit position list of a sequence cut after that query's token."""
+    import copy
+    rng = np.random.default_rng(5)
+    for T in (2, 3, 4):
+        Hq = 3
+        lens = [T, T + 1, 37, 130, 261]
+        for S, W in ((0, 5), (3, 0), (2, 7), (40, 100), (128, 140), (1000, 1000)):
+            inp = make_custom(len(lens), T * Hq, lens, S, W, seed=int(rng.integers(1 << 30)),
+                              q_std=1.0, kv_std=1.0)
+            out, lse = run(inp, lib, q_len=T)
+            for b, L in enumerate(lens):
+                for t in range(T):
+                    Lt = L - (T - 1 - t)          # keys 0 .. Lt-1 are visible to query t
+                    positions = explicit_index_list(Lt, S, W)
+                    view = copy.copy(inp)
+                    view.q = inp.q[:, t * Hq:(t + 1) * Hq]
+                    ref_o, ref_l = library_attention(view, b, positions)
+                    close(out[b, t * Hq:(t + 1) * Hq], ref_o.numpy(), 1e-11, f"mq out T={T} b={b} t={t}")
+                    close(lse[b, t * Hq:(t + 1) * Hq], ref_l.numpy(), 1e-11, f"mq lse T={T} b={b} t={t}")
+
+
 def pin_fp8(lib=None):
     pin_dense_reduction(lib, kv_dtype="fp8")
     pin_poison(lib, kv_dtype="fp8")
@@ -385,4 +408,4 @@ def pin_fp8(lib=None):
 ALL_PINS = [pin_decoders, pin_retained_predicate, pin_worked_example, pin_dense_reduction,
             pin_bruteforce_tiny, pin_softmax_invariants, pin_page_permutation, pin_poison,
             pin_closed_forms, pin_merge_identity, pin_boundary_spikes,
-            pin_scale_and_value_slice, pin_fp8]
+            pin_scale_and_value_slice, pin_multi_query, pin_fp8]

@@ -32,6 +32,9 @@ MUTANTS = [
     ("fp8_inf_codes", "if (e == 0xF && m == 0x7)", "if (e == 0xF)"),
     ("bf16_shift", "(uint32_t)bits << 16;", "(uint32_t)bits << 15;"),
     ("empty_set_lse_zero", "lse[i] = -INFINITY;", "lse[i] = 0.0;"),
+    ("mq_query_index", "int32_t t = h / Hq;", "int32_t t = h % q_len;"),
+    ("mq_length_off_by_one", "int64_t L = L_seq - (q_len - 1 - t);", "int64_t L = L_seq - (q_len - t);"),
+    ("mq_not_causal", "int64_t L = L_seq - (q_len - 1 - t);", "int64_t L = L_seq;"),
     ("head_index", "q[((int64_t)b * H + h) * QK_DIM + d]", "q[((int64_t)b * H + (H - 1 - h)) * QK_DIM + d]"),
 ]
 
