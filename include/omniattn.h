@@ -69,6 +69,13 @@ typedef struct {
   int32_t num_splits_hint;   /* 0: the library balances work over the GPU's compute
                                 units.  n > 0: every sequence's retained tiles are cut
                                 into min(n, tiles) pieces (for tests of the split path) */
+  int32_t q_len;             /* queries per sequence (the query matrix of the first equation
+                                of 3.2.1 has K rows); 0 or 1: one.  T > 1: the queries are
+                                the last T tokens of the sequence (all already in the cache
+                                and counted in L_b >= T), query t = 0 .. T-1 sits at position
+                                L_b - T + t and sees the keys before and at it: the kept-set
+                                rule is applied to a sequence of length L_b - (T - 1 - t).
+                                q, out and lse then carry [B, T, H, ...] (query-major)    */
 } omniattn_problem_t;
 
 typedef struct omniattn_plan_s omniattn_plan_t; /* opaque, library-owned */
@@ -125,7 +132,8 @@ int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t til
  * split) the combine pass.  Asynchronous on `hip_stream`; allocates nothing and
  * does not synchronise.
  *
- *   q          device, bf16 [B, H, 576] contiguous (absorbed queries)
+ *   q          device, bf16 [B, H, 576] contiguous (absorbed queries); [B, T, H, 576]
+ *              for q_len = T > 1, and out / lse likewise [B, T, H, 512] / [B, T, H]
  *   kv_cache   device, bf16 or e4m3 bytes [num_pages, 128, 576] contiguous
  *   kv_scales  device, fp32 [num_pages, 128]; NULL unless kv_dtype is fp8
  *   page_table device, int32 [B, max_pages_per_seq]; entry i of row b is the

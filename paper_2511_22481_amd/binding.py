@@ -26,7 +26,7 @@ class Problem(ctypes.Structure):
         ("max_pages_per_seq", ctypes.c_int32), ("num_pages", ctypes.c_int64),
         ("sink", ctypes.c_int32), ("window", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
         ("kv_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
-        ("num_splits_hint", ctypes.c_int32),
+        ("num_splits_hint", ctypes.c_int32), ("q_len", ctypes.c_int32),
     ]
 
 
@@ -141,9 +141,9 @@ class Plan:
 
 def _problem(batch, num_heads, max_pages_per_seq, num_pages, sink, window, softmax_scale,
              kv_dtype=BF16, out_dtype=BF16, num_splits_hint=0, qk_dim=576, v_dim=512,
-             page_size=128):
+             page_size=128, q_len=0):
     return Problem(batch, num_heads, qk_dim, v_dim, page_size, max_pages_per_seq, num_pages,
-                   sink, window, softmax_scale, kv_dtype, out_dtype, num_splits_hint)
+                   sink, window, softmax_scale, kv_dtype, out_dtype, num_splits_hint, q_len)
 
 
 def _lens_array(seq_lens):
@@ -224,11 +224,14 @@ def omniattn_ring_append(seq_lens, new_rows, new_scales, seq_pages, kv_cache, kv
 def decode(q, kv_cache, kv_scales, page_table, seq_lens_host, sink, window, softmax_scale,
            out_dtype=None, num_splits_hint=0, plan=None):
     """Convenience wrapper: plan (unless given), allocate outputs/workspace with torch,
-    decode.  Returns (out, lse, plan)."""
+    decode.  Returns (out, lse, plan).  q [B, H, 576], or [B, T, H, 576] for T queries per
+    sequence (the last T tokens, causal); out and lse are shaped alike."""
     import torch
     if not q.is_cuda:
         raise OmniAttnError(-4, "omniattn runs on the GPU only: tensors must be CUDA tensors")
-    B, H, _ = q.shape
+    q_len = int(q.shape[1]) if q.dim() == 4 else 0
+    lead = tuple(q.shape[:-1])
+    B, H = int(q.shape[0]), int(q.shape[-2])
     fp8 = kv_cache.dtype == torch.float8_e4m3fn
     odt = torch.bfloat16 if out_dtype is None else out_dtype
     if plan is None:
@@ -237,9 +240,9 @@ def decode(q, kv_cache, kv_scales, page_table, seq_lens_host, sink, window, soft
                              sink=sink, window=window, softmax_scale=softmax_scale,
                              kv_dtype=FP8_E4M3 if fp8 else BF16,
                              out_dtype=FP32 if odt == torch.float32 else BF16,
-                             num_splits_hint=num_splits_hint)
-    out = torch.empty((B, H, 512), dtype=odt, device=q.device)
-    lse = torch.empty((B, H), dtype=torch.float32, device=q.device)
+                             num_splits_hint=num_splits_hint, q_len=q_len)
+    out = torch.empty(lead + (512,), dtype=odt, device=q.device)
+    lse = torch.empty(lead, dtype=torch.float32, device=q.device)
     ws = None
     if plan.workspace_bytes:
         ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=q.device)

@@ -162,7 +162,7 @@ int32_t omniattn_plan_get_segments(const omniattn_plan_t* plan, int32_t* buf, in
 int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t tile, int32_t* lo,
                              int32_t* hi) {
   if (!plan || !lo || !hi || b < 0 || b >= plan->hp.prob.batch) return OMNIATTN_EINVAL;
-  TileLayout tl = tile_layout(plan->hp.seq_lens[b], plan->hp.prob.sink, plan->hp.prob.window);
+  TileLayout tl = tile_layout(plan->hp.seq_lens[b], plan->hp.prob.sink, plan->hp.window_union);
   if (tile < 0 || tile >= tl.count()) return OMNIATTN_EINVAL;
   *lo = tl.logical(tile) * kTile;
   *hi = *lo + kTile;
@@ -203,7 +203,10 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   dp.part_o = workspace ? (char*)workspace + hp.part_rows_offset : nullptr;
   dp.units = plan->d_units;
   dp.segs = plan->d_segs;
-  dp.H = hp.prob.num_heads;
+  dp.H = hp.heads_total;
+  dp.Hq = hp.prob.num_heads;
+  dp.T = hp.q_len;
+  dp.Wu = hp.window_union;
   dp.max_pages = hp.prob.max_pages_per_seq;
   dp.S = hp.prob.sink;
   dp.W = hp.prob.window;

@@ -221,9 +221,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const int lane_s = fresh_lane();
     const int n32 = lane_s & 31;  // head within the wave's 32 (B / C column)
     const int g = lane_s >> 5;    // k-group of the MFMA operands
-    const TileLayout tl = tile_layout(L, p.S, p.W);
+    // Tiles cover the union of the queries' kept sets: [0, S) and the Wu = W + T - 1 positions
+    // ending at L (one query: Wu = W).
+    const TileLayout tl = tile_layout(L, p.S, p.Wu);
     const int n_tiles = sg.tile_hi - sg.tile_lo;
-    const int sink_end = p.S < L ? p.S : L;
+    // A tile counts as full when every query keeps all of its positions: the earliest query
+    // sees a sequence of length L0 = L - (T - 1) and has the earliest window end, the latest
+    // one the latest window start L - W.
+    const int L0 = L - (p.T - 1);
+    const int sink_end = p.S < L0 ? p.S : L0;
 
     auto tile_pos = [&](int it) { return tl.logical(sg.tile_lo + it) * kTile; };
     // ring position of a tile's bf16 stage (three stages when the fourth holds raw fp8 tiles)
@@ -232,7 +238,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     auto stage_of = [](int it) -> uint32_t { return FP8 ? (uint32_t)it % 3u : (uint32_t)it & (kStages - 1); };
     const uint32_t lds_rawbuf = lds0 + 3 * kStageBytes;
     auto tile_full = [&](int pos0) {
-      return (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L);
+      return (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L0);
     };
     // ---- tile loader: wave w fills rows [w * kRowsPerWave, ...) of stage it & 3 ----
     // A tile is fetched by kDmaPerTile direct-load instructions per wave.  Exactly that
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             const int c = ci - r * kChunksPerRow;
             const int row = row_w0 + r;
             u32x4 v = {0, 0, 0, 0};
-            if (retained(pos0 + row, L, p.S, p.W)) v = *(const u32x4*)(gbase + row * kRowBytes + (c << 4));
+            if (retained(pos0 + row, L, p.S, p.Wu)) v = *(const u32x4*)(gbase + row * kRowBytes + (c << 4));
             *LDS_PTR(u32x4, lbase + lds_chunk(row, c)) = v;
           }
         }
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           const int row = ci / (kQK / 16);
           const int cc = ci - row * (kQK / 16);
           u32x4 raw = {0, 0, 0, 0};
-          if (full || retained(pos0 + row, L, p.S, p.W)) raw = *(const u32x4*)(gbase + row * kQK + cc * 16);
+          if (full || retained(pos0 + row, L, p.S, p.Wu)) raw = *(const u32x4*)(gbase + row * kQK + cc * 16);
           uint32_t w[8];
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
@@ -320,7 +326,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc + 1)) = u32x4{w[4], w[5], w[6], w[7]};
         }
         if (tid < kTile) {
-          const bool ok = full || retained(pos0 + tid, L, p.S, p.W);
+          const bool ok = full || retained(pos0 + tid, L, p.S, p.Wu);
           *LDS_PTR(float, lds_scales + (it & 3) * kScaleBytes + tid * 4) = ok ? sbase[tid] : 0.f;
         }
       }
@@ -493,11 +499,21 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     };
     // Per-lane validity bits of a partial tile: bit i = element i is a retained position
     // (element i is token (i/4)*8 + g*4 + i%4 of the tile).
+    // With several queries per sequence the lane's head belongs to query tq, which sees a
+    // sequence of length L - (T - 1 - tq) (derived here, on the rare path, rather than kept in
+    // a register through the loop).
     auto valid_bits = [&](int pos0) -> uint32_t {
+      int Lq = L;
+      if (p.T > 1) {
+        const int l = fresh_lane();
+        int tq = (h0 + (l & 31)) / p.Hq;
+        tq = tq < p.T ? tq : p.T - 1;  // lanes past the last head
+        Lq = L - (p.T - 1 - tq);
+      }
       uint32_t m = 0;
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        m |= (uint32_t)retained(pos0 + (i >> 2) * 8 + g * 4 + (i & 3), L, p.S, p.W) << i;
+        m |= (uint32_t)retained(pos0 + (i >> 2) * 8 + g * 4 + (i & 3), Lq, p.S, p.W) << i;
       return m;
     };
     // Logits are used in the log2 domain relative to the reference: t = s * c - ref (one
@@ -666,7 +682,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               const uint32_t row = t >> 3;
               cv_t8 = t & 7;
               const uint32_t e_next = *LDS_PTR(uint32_t, lds_tiles + (it + 1) * 8);
-              cv_rowok = (e_next & 1) || retained(tile_pos(it + 1) + (int)row, L, p.S, p.W);
+              cv_rowok = (e_next & 1) || retained(tile_pos(it + 1) + (int)row, L, p.S, p.Wu);
               cv_src = lds_rawbuf + ((it + 1) & 1) * kRawTileBytes + row * kQK + cv_t8 * 16;
               const uint32_t o0 = row * kMainRowBytes + (((2 * cv_t8) ^ swz_main(row)) << 4);
               const uint32_t o1 = kTailBase + row * kTailRowBytes + (((2 * cv_t8) ^ swz_tail(row)) << 4);
@@ -674,7 +690,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               cv_d1 = st_next + (o0 ^ 16);
               cv_t0 = st_next + o1;
               cv_t1 = st_next + (o1 ^ 16);
-              if (cv_on && !(e_next & 1) && t < (uint32_t)kTile && !retained(tile_pos(it + 1) + (int)t, L, p.S, p.W))
+              if (cv_on && !(e_next & 1) && t < (uint32_t)kTile && !retained(tile_pos(it + 1) + (int)t, L, p.S, p.Wu))
                 *LDS_PTR(float, lds_scales + ((it + 1) & 3) * kScaleBytes + t * 4) = 0.f;
             }
             if constexpr (m >= 8 && m <= 28 && (m - 8) % 5 == 0) {
@@ -831,7 +847,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 
     // ---- epilogue: normalise, transpose through LDS, write whole rows ----
     l_run += __shfl_xor(l_run, 32);
-    const float inv = n_tiles > 0 ? 1.0f / l_run : 0.f;
+    // (l_run == 0: a head that keeps no position of this segment - possible only with several
+    // queries per sequence, for a late query in a segment of early positions)
+    const float inv = (n_tiles > 0 && l_run != 0.f) ? 1.0f / l_run : 0.f;
     const float lse = n_tiles > 0 ? (ref + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : -INFINITY;
     const bool final_out = sg.slot < 0;
     const uint32_t ost = lds0 + wave * kOutWaveBytes;  // this wave's staging rows

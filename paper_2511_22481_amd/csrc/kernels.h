@@ -18,7 +18,10 @@ struct DecodeParams {
   float* part_lse;  // [n_slots, head_block]
   const UnitHeader* units;
   const Segment* segs;
-  int H, max_pages, S, W, head_block, out_fp32, n_units;
+  int H;        // rows of q per sequence: heads x queries
+  int Hq, T;    // heads per query, queries per sequence (T >= 1)
+  int Wu;       // W + T - 1: window of the union of the queries' kept sets
+  int max_pages, S, W, head_block, out_fp32, n_units;
   float scale_log2;  // softmax_scale * log2(e)
 };
 

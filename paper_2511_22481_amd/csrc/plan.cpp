@@ -2,6 +2,7 @@
 #include "plan.h"
 
 #include <algorithm>
+#include <climits>
 #include <cstring>
 
 namespace omniattn {
@@ -78,9 +79,13 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
   if (prob.kv_dtype != OMNIATTN_BF16 && prob.kv_dtype != OMNIATTN_FP8_E4M3) return OMNIATTN_EUNSUPPORTED;
   if (prob.out_dtype != OMNIATTN_BF16 && prob.out_dtype != OMNIATTN_FP32) return OMNIATTN_EUNSUPPORTED;
   if (!(prob.softmax_scale == prob.softmax_scale)) return OMNIATTN_EINVAL;  // NaN
+  if (prob.q_len < 0 || prob.q_len > 64) return OMNIATTN_EINVAL;
+  const int q_len = prob.q_len > 1 ? prob.q_len : 1;
+  if ((int64_t)prob.num_heads * q_len > (1 << 20)) return OMNIATTN_EUNSUPPORTED;
   for (int b = 0; b < prob.batch; ++b) {
     int64_t L = seq_lens[b];
     if (L < 0) return OMNIATTN_EINVAL;
+    if (L > 0 && L < q_len) return OMNIATTN_EINVAL;  // every query needs its own token in the cache
     if ((L + kPage - 1) / kPage > prob.max_pages_per_seq) return OMNIATTN_EINVAL;
   }
 
@@ -90,7 +95,13 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
   // Always four waves (one per SIMD), 32 heads each; waves past the last head idle along.
   hp.waves = 4;
   hp.head_block = hp.waves * kHeadsPerWave;
-  hp.n_hb = (prob.num_heads + hp.head_block - 1) / hp.head_block;
+  hp.q_len = q_len;
+  hp.heads_total = prob.num_heads * q_len;
+  // Several causal queries: query t keeps [0, S) and the W positions ending at its own token.
+  // Over all queries that is [0, S) and (for W > 0) the W + q_len - 1 positions ending at L:
+  // tiles are laid out for that union, the kernel masks per query.
+  hp.window_union = prob.window > 0 ? (int)std::min<int64_t>((int64_t)prob.window + q_len - 1, INT32_MAX) : 0;
+  hp.n_hb = (hp.heads_total + hp.head_block - 1) / hp.head_block;
 
   std::vector<Item> items;
   items.reserve((size_t)prob.batch * hp.n_hb);
@@ -99,12 +110,12 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
   for (int b = 0; b < prob.batch; ++b) {
     int L = seq_lens[b];
     int64_t sink_end = std::min<int64_t>(prob.sink, L);
-    int64_t win_lo = std::max<int64_t>((int64_t)L - prob.window, 0);
+    int64_t win_lo = std::max<int64_t>((int64_t)L - hp.window_union, 0);
     hp.retained_tokens += (win_lo <= sink_end) ? L : sink_end + (L - win_lo);
   }
   for (int hb = 0; hb < hp.n_hb; ++hb)
     for (int b = 0; b < prob.batch; ++b) {
-      int n = tile_layout(seq_lens[b], prob.sink, prob.window).count();
+      int n = tile_layout(seq_lens[b], prob.sink, hp.window_union).count();
       items.push_back({b, hb, n});
       total_cost += n + kSegFixedCost;
     }

@@ -88,6 +88,9 @@ struct HostPlan {
   int waves = 0;        // waves per work group; each owns 32 heads
   int head_block = 0;   // heads per work unit = 32 * waves
   int n_hb = 0;         // head blocks per sequence
+  int q_len = 1;          // queries per sequence
+  int heads_total = 0;    // q_len * num_heads rows of q per sequence ("virtual heads")
+  int window_union = 0;   // window + q_len - 1: the union of the queries' windows ends at L
   int64_t retained_tokens = 0;
   int max_splits = 1;
   std::vector<int32_t> seq_lens;

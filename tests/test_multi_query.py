@@ -1,0 +1,101 @@
+"""Several causal queries per sequence (q_len = T: the last T tokens of each sequence).
+
+Query t sits at position L - T + t and sees a sequence cut after its own token; the kept-set
+rule (sinks + recent window) applies to that shorter sequence.  CPU: the plan's tiles cover the
+union of the queries' kept sets.  GPU: element-wise parity with the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_22481_amd as oa
+import oracle
+import parity
+from workloads import make_custom
+
+PAGE = 128
+
+
+def retained(j, L, S, W):
+    return 0 <= j < L and (j < S or j >= L - W)
+
+
+@pytest.mark.parametrize("T", [2, 3, 4])
+def test_plan_covers_every_querys_kept_set(T):
+    lens = [T, T + 5, 100, 257, 1000, 4500, 0]
+    for S, W in ((0, 1), (70, 0), (64, 300), (128, 129), (5000, 5000)):
+        plan = oa.omniattn_plan_host(lens, num_cus=64, batch=len(lens), num_heads=16, max_pages_per_seq=40,
+                                     num_pages=400, sink=S, window=W, softmax_scale=0.1, q_len=T)
+        tt = plan.tile_tokens
+        covered = [set() for _ in lens]
+        for sg in plan.segments():
+            for tile in range(sg["tile_lo"], sg["tile_hi"]):
+                a, e = plan.tile_range(sg["b"], tile)
+                covered[sg["b"]].update(range(a, min(e, sg["L"])))
+        for b, L in enumerate(lens):
+            need = {j for t in range(T) for j in range(L) if retained(j, L - (T - 1 - t), S, W)}
+            assert need <= covered[b]
+            # and nothing but whole tiles around the union: each covered tile holds a needed position
+            for j in covered[b]:
+                assert any(k in need for k in range(j // tt * tt, j // tt * tt + tt))
+    # a sequence shorter than the number of queries is refused
+    with pytest.raises(oa.OmniAttnError):
+        oa.omniattn_plan_host([1, 10], num_cus=8, batch=2, num_heads=16, max_pages_per_seq=4, num_pages=8,
+                              sink=4, window=4, softmax_scale=0.1, q_len=2)
+
+
+def _run(inp, T, H, **kw):
+    B = inp.q.shape[0]
+    q4 = inp.q.reshape(B, T, H, 576)
+    out, lse, plan = oa.decode(q4, inp.kv_cache, inp.kv_scales, inp.page_table, inp.seq_lens_host,
+                               inp.sink, inp.window, inp.softmax_scale, **kw)
+    torch.cuda.synchronize()
+    assert out.shape == (B, T, H, 512) and lse.shape == (B, T, H)
+    return out.reshape(B, T * H, 512), lse.reshape(B, T * H), plan
+
+
+def _check(inp, out, lse, T, what, row_rel_l2=1e-2):
+    ref_o, ref_l = oracle.oracle_decode(inp.q, inp.kv_cache, inp.kv_scales, inp.page_table,
+                                        inp.seq_lens_host, inp.sink, inp.window, inp.softmax_scale,
+                                        kv_dtype=inp.kv_dtype, q_len=T)
+    e = parity.errors(out, lse, ref_o, ref_l)
+    scale = max(1.0, float(np.nanmax(np.abs(ref_o))))
+    assert e["max_abs"] <= parity.MAX_ABS * scale and e["rel_l2"] <= parity.REL_L2[inp.kv_dtype], (what, e)
+    assert e["lse_abs"] <= parity.LSE_ABS and e["worst_row_rel_l2"] <= row_rel_l2, (what, e)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("T,H", [(2, 16), (2, 128), (3, 48), (4, 128)])
+def test_multi_query_parity(T, H):
+    lens = [T, T + 1, 31, 64, 200, 333, 1000, 2500]
+    for S, W in ((0, 40), (64, 0), (50, 130), (128, 256), (33, 65), (4000, 4000)):
+        inp = parity.to_device(make_custom(len(lens), T * H, lens, S, W, seed=40 + T + S, q_std=0.7, kv_std=0.7))
+        out, lse, _ = _run(inp, T, H)
+        _check(inp, out, lse, T, f"T={T} H={H} S={S} W={W}")
+
+
+@pytest.mark.gpu
+def test_multi_query_split_fp32_and_fp8():
+    T, H = 3, 64
+    lens = [900, 2176, 130, 4000]
+    inp = parity.to_device(make_custom(len(lens), T * H, lens, 64, 512, seed=77, q_std=0.5, kv_std=0.5))
+    base, lse0, _ = _run(inp, T, H, out_dtype=torch.float32)
+    _check(inp, base, lse0, T, "mq fp32")
+    for hint in (2, 5, 64):      # pieces whose early tiles some queries do not see at all
+        out, lse, plan = _run(inp, T, H, out_dtype=torch.float32, num_splits_hint=hint)
+        _check(inp, out, lse, T, f"mq split {hint}")
+        assert float((out - base).abs().max()) <= 5e-5 * max(1.0, float(base.abs().max()))
+    inp8 = parity.to_device(make_custom(len(lens), T * H, lens, 64, 512, seed=78, kv_dtype="fp8", q_std=0.3, kv_std=1.0))
+    out, lse, _ = _run(inp8, T, H)
+    _check(inp8, out, lse, T, "mq fp8", row_rel_l2=2e-2)
+
+
+@pytest.mark.gpu
+def test_one_query_is_the_plain_decode():
+    inp = parity.to_device(make_custom(3, 32, [500, 77, 1300], 40, 200, seed=9, q_std=0.5, kv_std=0.5))
+    out1, lse1, _ = parity.run_gpu(inp)
+    B = 3
+    out, lse, _ = oa.decode(inp.q.reshape(B, 1, 32, 576), inp.kv_cache, inp.kv_scales, inp.page_table,
+                            inp.seq_lens_host, inp.sink, inp.window, inp.softmax_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out.reshape(B, 32, 512), out1) and torch.equal(lse.reshape(B, 32), lse1)
