@@ -9,6 +9,7 @@ from .generate import (  # noqa: F401
     Inputs,
     make_inputs,
     make_custom,
+    make_planted,
     quantize_fp8_per_token,
     poison_unretained,
 )

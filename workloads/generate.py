@@ -133,6 +133,35 @@ def make_custom(batch: int, heads: int, seq_lens: Sequence[int], sink: int, wind
                   softmax_scale=float(softmax_scale), kv_dtype=kv_dtype)
 
 
+def make_planted(batch: int, heads: int, ctx: int, *, sink_tokens: int = 4, sink_logit: float = 6.0,
+                 recency_logit: float = 6.0, recency_tau: float = 400.0, noise_std: float = 1.0,
+                 seed: int = 0, device="cpu") -> Inputs:
+    """A decode problem whose dense attention has the shape the paper's premise describes
+    (section 3.2.1: the first tokens and the most recent tokens carry most of the attention
+    mass): on top of Gaussian logits of standard deviation `noise_std`, position j gets
+    `sink_logit` if j < sink_tokens and `recency_logit * exp(-(L-1-j)/recency_tau)`.
+
+    The profile is planted through one coordinate: q[..., 575] = 1 and the cache row's last
+    coordinate holds profile / softmax_scale; the other coordinates are random.  sink/window
+    are left at "keep everything"; callers overwrite them.
+    """
+    scale = 192.0 ** -0.5
+    # Gaussian part: logits = scale * sum_d q_d k_d over 575 coordinates with std noise_std
+    std = (noise_std / (scale * (QK_DIM - 1) ** 0.5)) ** 0.5
+    inp = make_custom(batch, heads, [ctx] * batch, 0, ctx, seed=seed, q_std=std, kv_std=std,
+                      softmax_scale=scale, device=device)
+    j = torch.arange(ctx, dtype=torch.float32)
+    profile = recency_logit * torch.exp(-(ctx - 1 - j) / recency_tau)
+    profile[:sink_tokens] += sink_logit
+    col = (profile / scale).to(torch.bfloat16)
+    inp.q[:, :, QK_DIM - 1] = 1.0
+    for b in range(batch):
+        for pg in range((ctx + PAGE - 1) // PAGE):
+            n = min(PAGE, ctx - pg * PAGE)
+            inp.kv_cache[int(inp.page_table[b, pg]), :n, QK_DIM - 1] = col[pg * PAGE: pg * PAGE + n].to(inp.kv_cache.device)
+    return inp
+
+
 def make_inputs(cfg: Config, device="cpu", *, batch: Optional[int] = None,
                 seed_offset: int = 0) -> Inputs:
     """Inputs for one of the named workloads (optionally only its first
