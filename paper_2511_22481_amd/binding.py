@@ -98,13 +98,15 @@ class Plan:
     def __init__(self, handle, problem):
         self._h = handle
         self.problem = problem
+        # kept on the object: at interpreter shutdown module globals may be gone before __del__ runs
+        self._destroy = load_library().omniattn_plan_destroy
 
     def __del__(self):
         self.destroy()
 
     def destroy(self):
         if getattr(self, "_h", None):
-            load_library().omniattn_plan_destroy(self._h)
+            self._destroy(self._h)
             self._h = None
 
     @property

@@ -66,7 +66,9 @@ constexpr int kRawTileBytes = kTile * kQK;  // 18,432
 static_assert(2 * kRawTileBytes <= kStageBytes, "raw buffers fit the fourth stage");
 constexpr int kTileTabBytes = kMaxSegTiles * 8;  // first global byte of every tile of the segment
 constexpr int kJunkBytes = 4096;  // target of the direct loads issued for tiles that do not exist
-constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16 + kTileTabBytes + kJunkBytes;  // 16: retry flag
+constexpr int kZeroBytes = kQK;    // fp8: a row of zero codes, read in place of rows outside the retained set
+constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16 + kTileTabBytes + kJunkBytes + kZeroBytes;  // 16: retry flag
+static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
 __host__ __device__ constexpr int swz_main(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 __host__ __device__ constexpr int swz_tail(int r) { return (r >> 1) & 7; }
 // byte offset of chunk c (0..71) of row r inside a stage
@@ -159,6 +161,14 @@ __device__ __forceinline__ void wait_vm() {
 // summing a million terms) the work group runs the same segment code a second time
 // with r = that exact maximum, which cannot overflow.
 constexpr float kRefSlack = 64.f;
+
+// Eight e4m3 codes (two dwords) to eight bf16: the conversion is exact, bf16 holds every e4m3 value.
+__device__ __forceinline__ u32x4 widen8(uint32_t lo, uint32_t hi) {
+  return u32x4{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false)),
+               __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true)),
+               __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false)),
+               __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true))};
+}
 constexpr int kXcds = 8;  // accelerator complex dies: work group i runs on XCD i % 8
 
 template <int WAVES, bool FP8>
@@ -169,6 +179,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const uint32_t lds_flag = lds_scales + kStages * kScaleBytes;
   const uint32_t lds_tiles = lds_flag + 16;
   const uint32_t lds_junk = lds_tiles + kTileTabBytes;
+  const uint32_t lds_zero = lds_junk + kJunkBytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -204,6 +215,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const u32x4* hdr = (const u32x4*)(p.units + unit);
   const u32x4 hdr0 = hdr[0], hdr1 = hdr[1], hdr2 = hdr[2];
   const int seg_lo = __builtin_amdgcn_readfirstlane(hdr0.x), seg_hi = __builtin_amdgcn_readfirstlane(hdr0.y);
+  if constexpr (FP8) {  // published by the first barrier of the first segment
+    if (tid < kZeroBytes / 4) *LDS_PTR(uint32_t, lds_zero + tid * 4) = 0u;
+  }
 
   for (int si = seg_lo; si < seg_hi; ++si) {
     u32x4 sg_a = hdr1, sg_b = hdr2;
@@ -312,22 +326,14 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           const int cc = ci - row * (kQK / 16);
           u32x4 raw = {0, 0, 0, 0};
           if (full || retained(pos0 + row, L, p.S, p.Wu)) raw = *(const u32x4*)(gbase + row * kQK + cc * 16);
-          uint32_t w[8];
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(raw[k], false);
-            f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(raw[k], true);
-            bf16x2 blo = {(__bf16)lo.x, (__bf16)lo.y};
-            bf16x2 bhi = {(__bf16)hi.x, (__bf16)hi.y};
-            w[2 * k] = __builtin_bit_cast(uint32_t, blo);
-            w[2 * k + 1] = __builtin_bit_cast(uint32_t, bhi);
-          }
-          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc)) = u32x4{w[0], w[1], w[2], w[3]};
-          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc + 1)) = u32x4{w[4], w[5], w[6], w[7]};
+          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc)) = widen8(raw[0], raw[1]);
+          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc + 1)) = widen8(raw[2], raw[3]);
         }
+        // (a position outside the retained set gets scale 1: its logit is set to -inf before the
+        // scale is applied and its weight is 0, so any finite positive value does)
         if (tid < kTile) {
           const bool ok = full || retained(pos0 + tid, L, p.S, p.Wu);
-          *LDS_PTR(float, lds_scales + (it & 3) * kScaleBytes + tid * 4) = ok ? sbase[tid] : 0.f;
+          *LDS_PTR(float, lds_scales + (it & 3) * kScaleBytes + tid * 4) = ok ? sbase[tid] : 1.f;
         }
       }
       return ts;
@@ -432,9 +438,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     issue_tile(0);
     issue_tile(1);
 
-    // LDS fragment requests kept in flight (the fp8 kernel needs the registers for the
-    // widening pass and gets by with a shorter ring); must be 8 or 4
-    constexpr int kRing = FP8 ? 4 : 8;
+    // LDS fragment requests kept in flight (the hand-over between iterations is written for 8)
+    constexpr int kRing = 8;
     constexpr int kNK = kQK / 16;       // 36 MFMAs for S^T
     constexpr int kNV = 2 * (kV / 32);  // 32 MFMAs for O^T
 
@@ -661,64 +666,53 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           const TileSrc ts = prep_tile_e(it + 2, e_lo, e_hi);
           uint32_t full_word = 1;
           float lsum = 0.f, mt = -INFINITY;
+          // fp8: the scales of the lane's 16 tokens, four at a time, each group requested while the
+          // group before it is in use; a scale multiplies the raw logit and, again, the weight
           [[maybe_unused]] uint32_t sc_base = 0;
-          [[maybe_unused]] f32x4 sc4 = {0.f, 0.f, 0.f, 0.f};
+          [[maybe_unused]] f32x4 sc4[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
           bf16x8 pf[2];  // weights of tile it-1, taken over from pn behind MFMA 2
           // fp8: the raw bytes of tile it+1 (arrived and published by the previous iteration's
           // barrier) are widened to bf16 into that tile's stage while S^T of tile `it` runs.
-          // Thread t handles row t / 8 and the 16-code chunks (t % 8) + 8 j, j = 0 .. 4 (the
-          // row has 36): chunk j is requested behind MFMA 8 + 5 j and stored, as two bf16
-          // chunks, behind MFMA 11 + 5 j.  Rows outside the retained set (partial tiles) are
-          // stored as zeros and their scales are zeroed: their contents are unspecified.
-          [[maybe_unused]] uint32_t cv_src = 0, cv_d0 = 0, cv_d1 = 0, cv_t0 = 0, cv_t1 = 0, cv_t8 = 0;
-          [[maybe_unused]] bool cv_on = false, cv_rowok = true;
-          [[maybe_unused]] u32x4 cv_raw = {0, 0, 0, 0};
+          // Thread t handles row t / 8 and the nine 8-code pieces (t % 8) + 8 k of it (the row has
+          // 72): piece k is requested behind MFMA 6 + 3 k and stored, as one bf16 chunk, behind
+          // MFMA 8 + 3 k.  Every thread does the same nine steps for every tile index, without a
+          // branch: past the segment's end the pass turns stale bytes into a stage nobody reads,
+          // and a row outside the retained set (partial tiles; its contents are unspecified) is
+          // read from a row of zero codes instead.
+          [[maybe_unused]] uint32_t cv_src = 0, cv_d = 0, cv_dt = 0;
+          [[maybe_unused]] u32x2 cv_raw = {0, 0};
           auto convert_step = [&](auto m_tag) {
             constexpr int m = decltype(m_tag)::value;
-            if constexpr (m == 6) {
-              cv_on = it + 1 < n_tiles;
+            if constexpr (m == 3) {
               uint32_t t = tid;
               asm volatile("" : "+v"(t));
-              const uint32_t row = t >> 3;
-              cv_t8 = t & 7;
-              const uint32_t e_next = *LDS_PTR(uint32_t, lds_tiles + (it + 1) * 8);
-              cv_rowok = (e_next & 1) || retained(tile_pos(it + 1) + (int)row, L, p.S, p.Wu);
-              cv_src = lds_rawbuf + ((it + 1) & 1) * kRawTileBytes + row * kQK + cv_t8 * 16;
-              const uint32_t o0 = row * kMainRowBytes + (((2 * cv_t8) ^ swz_main(row)) << 4);
-              const uint32_t o1 = kTailBase + row * kTailRowBytes + (((2 * cv_t8) ^ swz_tail(row)) << 4);
-              cv_d0 = st_next + o0;
-              cv_d1 = st_next + (o0 ^ 16);
-              cv_t0 = st_next + o1;
-              cv_t1 = st_next + (o1 ^ 16);
-              if (cv_on && !(e_next & 1) && t < (uint32_t)kTile && !retained(tile_pos(it + 1) + (int)t, L, p.S, p.Wu))
-                *LDS_PTR(float, lds_scales + ((it + 1) & 3) * kScaleBytes + t * 4) = 0.f;
-            }
-            if constexpr (m >= 8 && m <= 28 && (m - 8) % 5 == 0) {
-              constexpr int j = (m - 8) / 5;
-              if (cv_on && (j < 4 || cv_t8 < 4)) cv_raw = *LDS_PTR(u32x4, cv_src + 128 * j);
-            }
-            if constexpr (m >= 11 && m <= 31 && (m - 11) % 5 == 0) {
-              constexpr int j = (m - 11) / 5;
-              if (cv_on && (j < 4 || cv_t8 < 4)) {
-                uint32_t w[8];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                  const uint32_t code = cv_rowok ? cv_raw[k] : 0u;
-                  f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(code, false);
-                  f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(code, true);
-                  bf16x2 blo = {(__bf16)lo.x, (__bf16)lo.y};
-                  bf16x2 bhi = {(__bf16)hi.x, (__bf16)hi.y};
-                  w[2 * k] = __builtin_bit_cast(uint32_t, blo);
-                  w[2 * k + 1] = __builtin_bit_cast(uint32_t, bhi);
-                }
-                if constexpr (j < 4) {
-                  *LDS_PTR(u32x4, cv_d0 + 256 * j) = u32x4{w[0], w[1], w[2], w[3]};
-                  *LDS_PTR(u32x4, cv_d1 + 256 * j) = u32x4{w[4], w[5], w[6], w[7]};
-                } else {
-                  *LDS_PTR(u32x4, cv_t0) = u32x4{w[0], w[1], w[2], w[3]};
-                  *LDS_PTR(u32x4, cv_t1) = u32x4{w[4], w[5], w[6], w[7]};
-                }
+              const uint32_t row = t >> 3, t8 = t & 7;
+              const uint32_t e_next = __builtin_amdgcn_readfirstlane(
+                  *LDS_PTR(uint32_t, lds_tiles + (it + 1 < kMaxSegTiles ? it + 1 : kMaxSegTiles - 1) * 8));
+              const bool next_full = e_next & 1;  // wave-uniform
+              const int pos_next = tile_pos(it + 1);
+              const bool rowok = next_full || retained(pos_next + (int)row, L, p.S, p.Wu);
+              cv_src = (rowok ? lds_rawbuf + ((it + 1) & 1) * kRawTileBytes + row * kQK : lds_zero) + t8 * 8;
+              const uint32_t sw = swz_main(row);
+              cv_d = st_next + row * kMainRowBytes + (((t8 ^ (sw & 7)) | (sw & 8)) << 4);
+              cv_dt = st_next + kTailBase + row * kTailRowBytes + ((t8 ^ swz_tail(row)) << 4);
+              // scales of positions outside the retained set: see the synchronous fill of tiles 0, 1
+              if (!next_full && it + 1 < n_tiles) {
+                if (t < (uint32_t)kTile && !retained(pos_next + (int)t, L, p.S, p.Wu))
+                  *LDS_PTR(float, lds_scales + ((it + 1) & 3) * kScaleBytes + t * 4) = 1.f;
               }
+            }
+            if constexpr (m >= 6 && m <= 30 && (m - 6) % 3 == 0) {
+              constexpr int k = (m - 6) / 3;
+              cv_raw = *LDS_PTR(u32x2, cv_src + 64 * k);
+            }
+            if constexpr (m >= 8 && m <= 32 && (m - 8) % 3 == 0) {
+              constexpr int k = (m - 8) / 3;
+              const u32x4 w = widen8(cv_raw.x, cv_raw.y);
+              // piece k is bf16 chunk t8 + 8 k of the row: chunk position (t8 + 8 k) ^ swizzle
+              if constexpr (k == 8) *LDS_PTR(u32x4, cv_dt) = w;
+              else if constexpr (k & 1) *LDS_PTR(u32x4, (cv_d ^ 128u) + (k >> 1) * 256) = w;
+              else *LDS_PTR(u32x4, cv_d + (k >> 1) * 256) = w;
             }
           };
           // One MFMA and what is issued behind it; m is a compile-time constant.
@@ -778,17 +772,18 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               if constexpr (FP8) wait_vm<0>();  // the raw bytes of tile it+2 (and tile it+1 is widened)
               else wait_tile();
               __syncthreads();
-              if constexpr (kRing == 8) {
 #pragma unroll
-                for (int d = 4; d < 8; ++d) fr[d] = load_k(ka, d);
-              }
+              for (int d = 4; d < 8; ++d) fr[d] = load_k(ka, d);
             }
             constexpr int j = m - kNK;
+            if constexpr (FP8 && m == 33) {
+              sc_base = scale_base(it & 3);
+              sc4[0] = tok_scale4(sc_base, 0);
+            }
             if constexpr (j == 0) {
-              if (FP8 || !(full_word & 1)) {  // wave-uniform; rare for a bf16 cache
+              if (!(full_word & 1)) {  // wave-uniform and rare
                 settle_s(s);
-                if constexpr (FP8) scale_logits(s, it & 3);
-                if (!(full_word & 1)) mask_partial(s, tile_pos(it));
+                mask_partial(s, tile_pos(it));
               }
             }
             // S^T may be read by the vector ALU 12 instructions after its last MFMA: the
@@ -798,15 +793,16 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             if constexpr (j >= kFirst) {
               constexpr int i = ((j - kFirst) * 16) / (kNV - kFirst), i1 = ((j + 1 - kFirst) * 16) / (kNV - kFirst);
               if constexpr (i1 > i) {  // at most one element per MFMA
-                const float t = fmaf(s[i], c, -ref);
+                float raw = s[i];
+                if constexpr (FP8) {
+                  if constexpr ((i & 3) == 0 && i < 12) sc4[((i >> 2) + 1) & 1] = tok_scale4(sc_base, (i >> 2) + 1);
+                  raw *= sc4[(i >> 2) & 1][i & 3];
+                }
+                const float t = fmaf(raw, c, -ref);
                 mt = fmaxf(mt, t);
                 float e = __builtin_amdgcn_exp2f(t);
                 lsum += e;
-                if constexpr (FP8) {
-                  if constexpr (i == 0) sc_base = scale_base(it & 3);
-                  if constexpr ((i & 3) == 0) sc4 = tok_scale4(sc_base, i >> 2);
-                  e *= sc4[i & 3];
-                }
+                if constexpr (FP8) e *= sc4[(i >> 2) & 1][i & 3];
                 pn[i >> 3][i & 7] = (__bf16)e;
               }
             }
