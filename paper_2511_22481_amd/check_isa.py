@@ -36,9 +36,6 @@ def check(asm_text, kernel_filter="decode_kernel"):
     problems = []
     # 1. no register spill traffic inside a basic block that runs part of the MFMA stream: a
     #    spill reload waits on the vector-memory counter and would drain the tile prefetch.
-    #    (Only the bf16-cache kernel prefetches tiles with direct loads; the fp8 kernel fills
-    #    its tiles through registers at the top of an iteration, so a reload there costs time
-    #    but drains nothing.)
     block, name, in_k = [], None, False
     for raw in asm_text.splitlines() + ["end:"]:
         line = raw.split(";")[0].strip()
@@ -48,7 +45,7 @@ def check(asm_text, kernel_filter="decode_kernel"):
             if in_k and first is not None and sum(l.startswith("v_mfma") for l in block[first:]) >= 8:
                 problems.append(f"register spill traffic in front of MFMAs in block {name}")
             if not line.startswith("."):
-                in_k = kernel_filter in line and "ELb1E" not in line
+                in_k = kernel_filter in line
             block, name = [], line
         elif line:
             block.append(line)
