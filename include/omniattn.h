@@ -130,7 +130,8 @@ int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t til
  * Steps a3-a9: gather retained tiles through the page table, QK^T, masking of
  * partial tiles, online softmax, PV, normalisation, and (when some sequence was
  * split) the combine pass.  Asynchronous on `hip_stream`; allocates nothing and
- * does not synchronise.
+ * does not synchronise.  The current HIP device must be the one the plan was made on
+ * (OMNIATTN_EINVAL otherwise).
  *
  *   q          device, bf16 [B, H, 576] contiguous (absorbed queries); [B, T, H, 576]
  *              for q_len = T > 1, and out / lse likewise [B, T, H, 512] / [B, T, H]

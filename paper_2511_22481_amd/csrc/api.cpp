@@ -38,8 +38,20 @@ int hip_fail(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return hip_fail(e_, #call); \
   } while (0)
 
-std::once_flag g_init_once;
-hipError_t g_init_status = hipSuccess;
+// The kernels' dynamic-LDS limit is a per-device function attribute: set once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_init_mutex;
+bool g_init_done[kMaxDevices] = {};
+
+int init_device(int dev) {
+  if (dev < 0 || dev >= kMaxDevices) return OMNIATTN_EINVAL;
+  std::lock_guard<std::mutex> lock(g_init_mutex);
+  if (g_init_done[dev]) return OMNIATTN_OK;
+  hipError_t e = init_kernels();
+  if (e != hipSuccess) return hip_fail(e, "kernel attribute setup");
+  g_init_done[dev] = true;
+  return OMNIATTN_OK;
+}
 
 void free_device(omniattn_plan_s* pl) {
   if (pl->d_units) (void)hipFree(pl->d_units);
@@ -100,20 +112,22 @@ int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
   OA_HIP(hipGetDevice(&dev));
   int cus = 0;
   OA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  std::call_once(g_init_once, [] { g_init_status = init_kernels(); });
-  if (g_init_status != hipSuccess) return hip_fail(g_init_status, "kernel attribute setup");
+  int rc = init_device(dev);
+  if (rc != OMNIATTN_OK) return rc;
 
   omniattn_plan_s* pl = nullptr;
-  int rc = make_plan(&pl, prob, seq_lens_host, cus > 0 ? cus : 256);
+  rc = make_plan(&pl, prob, seq_lens_host, cus > 0 ? cus : 256);
   if (rc != OMNIATTN_OK) return rc;
   pl->device = dev;
-  {
+  try {
     std::vector<UnitHeader> hdr(pl->hp.unit_seg.size() - 1);
     for (size_t u = 0; u + 1 < pl->hp.unit_seg.size(); ++u) {
       hdr[u] = UnitHeader{pl->hp.unit_seg[u], pl->hp.unit_seg[u + 1], 0, 0, Segment{}};
       if (hdr[u].seg_lo < hdr[u].seg_hi) hdr[u].first = pl->hp.segs[hdr[u].seg_lo];
     }
     rc = upload(&pl->d_units, hdr);
+  } catch (const std::bad_alloc&) {
+    rc = OMNIATTN_ENOMEM;
   }
   if (rc == OMNIATTN_OK) rc = upload(&pl->d_segs, pl->hp.segs);
   if (rc == OMNIATTN_OK) rc = upload(&pl->d_combine, pl->hp.combine);
@@ -182,6 +196,9 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
                           void* ev_begin, void* ev_main_end, void* ev_end) {
   if (!plan || !q || !kv_cache || !page_table || !out || !lse) return OMNIATTN_EINVAL;
   if (!plan->on_device) return OMNIATTN_EINVAL;
+  int dev = -1;
+  OA_HIP(hipGetDevice(&dev));
+  if (dev != plan->device) return OMNIATTN_EINVAL;  // the plan's metadata lives on another device
   const HostPlan& hp = plan->hp;
   const bool fp8 = hp.prob.kv_dtype == OMNIATTN_FP8_E4M3;
   if (fp8 && !kv_scales) return OMNIATTN_EINVAL;
