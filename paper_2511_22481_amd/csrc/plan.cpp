@@ -113,8 +113,10 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
     int64_t win_lo = std::max<int64_t>((int64_t)L - hp.window_union, 0);
     hp.retained_tokens += (win_lo <= sink_end) ? L : sink_end + (L - win_lo);
   }
-  for (int hb = 0; hb < hp.n_hb; ++hb)
-    for (int b = 0; b < prob.batch; ++b) {
+  // sequence-major: the head blocks of one sequence read the same tiles; as neighbours they
+  // land on one XCD (see the unit mapping in the kernel) and share its L2
+  for (int b = 0; b < prob.batch; ++b)
+    for (int hb = 0; hb < hp.n_hb; ++hb) {
       int n = tile_layout(seq_lens[b], prob.sink, hp.window_union).count();
       items.push_back({b, hb, n});
       total_cost += n + kSegFixedCost;
