@@ -903,6 +903,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
 // (combine item, group of 4 heads); 64 lanes x 8 columns cover one head row.  Partials
 // are taken four at a time, all their loads in flight together, and folded into a
 // running (maximum, sum, row) triple, so any number of partials takes one pass.
+// One instance per output type: with both in one kernel the registers of the fp32 path
+// cost the bf16 path a third of its waves in flight, and this kernel lives on those.
+template <bool OUT_FP32>
 __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
   const CombineItem it = p.items[blockIdx.x];
   const int hl = blockIdx.y * 4 + (threadIdx.x >> 6);
@@ -921,7 +924,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
       const bool ok = s0 + k < it.nslots;
       const size_t row = (size_t)(it.slot0 + (ok ? s0 + k : 0)) * p.head_block + hl;
       l[k] = ok ? p.part_lse[row] : -INFINITY;
-      if (p.out_fp32) {
+      if constexpr (OUT_FP32) {
         const f32x4* src = (const f32x4*)((const float*)p.part_o + row * kV + lane * 8);
         ra[k] = src[0];
         rb[k] = src[1];
@@ -941,7 +944,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
     for (int k = 0; k < kBatch; ++k) {
       const float w = __expf(l[k] - mb);  // 0 for a slot past the end
       z += w;
-      if (p.out_fp32) {
+      if constexpr (OUT_FP32) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           o[c] = fmaf(w, ra[k][c], o[c]);
@@ -957,7 +960,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
   const float inv = z > 0.f ? 1.0f / z : 0.f;
   const size_t orow = (size_t)it.b * p.H + head;
   if (lane == 0) p.lse[orow] = z > 0.f ? m + __logf(z) : -INFINITY;
-  if (p.out_fp32) {
+  if constexpr (OUT_FP32) {
     float* dst = (float*)p.out + orow * kV + lane * 8;
     *(f32x4*)dst = f32x4{o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
     *(f32x4*)(dst + 4) = f32x4{o[4] * inv, o[5] * inv, o[6] * inv, o[7] * inv};
@@ -996,7 +999,8 @@ hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units
 hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t stream) {
   if (n_items <= 0) return hipSuccess;
   dim3 grid(n_items, (p.head_block + 3) / 4), block(256);
-  hipLaunchKernelGGL(combine_kernel, grid, block, 0, stream, p);
+  if (p.out_fp32) hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, stream, p);
+  else hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, stream, p);
   return hipGetLastError();
 }
 
