@@ -28,7 +28,7 @@ WORKLOAD = "r1_b64_32k"
 # HBM bytes per launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file (profiles/decode_kernel_r1_b64_32k_hbm_counters.md), scaled by what the same
 # counters read for a 1 GiB device copy.  To be re-taken whenever the kernel changes.
-MEASURED_TRAFFIC_BYTES = {"r1_b64_32k": 170_599_800 + 36_044_800}
+MEASURED_TRAFFIC_BYTES = {"r1_b64_32k": 170_635_500 + 36_044_800}
 
 
 def algorithmic_bytes(retained_tokens, batch, heads, kv_dtype):
