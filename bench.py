@@ -51,8 +51,8 @@ def main():
                          "calibration kernel for HBM byte counters collected with rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by batch with no "
-              "exchange step; see DESIGN.md). Use --gpus 1.", file=sys.stderr)
+        print("bench.py: this library runs on one GPU only (the path shards by batch with no "
+              "exchange step between GPUs). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
