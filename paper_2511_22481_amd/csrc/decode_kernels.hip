@@ -261,7 +261,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     // The count of loads in flight per tile is therefore a constant, which is what the
     // vmcnt-based wait_tile relies on, and the loop needs no branch per load.
     struct TileSrc {
-      const uint8_t* gbase;   // first byte of the tile's rows in the cache (or any valid address)
+      const uint8_t* gbase;   // first byte of the tile's rows in the cache (placeholder loads: page 0 of the cache)
       uint32_t lmain, ltail;  // LDS destinations of row 0 (main part, tail part)
       uint32_t mstride, tstride;  // 1024 / 128, or 0 for the junk target
       const float* sgbase;    // fp8: the tile's 32 scales in global memory
@@ -269,7 +269,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     };
     auto prep_tile_e = [&](int it, uint32_t e_lo, uint32_t e_hi) -> TileSrc {
       TileSrc ts;
-      ts.gbase = (const uint8_t*)p.q;
+      // Placeholder loads read up to one tile's worth of bytes behind gbase: the cache's first
+      // page (128 rows) always holds that much, which a small q tensor does not.
+      ts.gbase = p.kv;
       ts.lmain = ts.ltail = lds_junk;
       ts.mstride = ts.tstride = 0;
       ts.sgbase = nullptr;
@@ -354,11 +356,11 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           const int c = wave + 4 * k;
           const bool real = ts.mstride != 0 && c < kRawTileBytes / 1024;
           dma_set_lds_base(real ? ts.lmain + c * 1024 : lds_junk);
-          dma16<0>(real ? ts.gbase : (const uint8_t*)p.q, (real ? c * 1024 : 0) + l16);
+          dma16<0>(real ? ts.gbase : p.kv, (real ? c * 1024 : 0) + l16);
         } else {  // the 32 scales (128 bytes): lanes 32..63 fetch the same words again
           const bool real = ts.mstride != 0 && wave == 0;
           dma_set_lds_base(real ? ts.lscale : lds_junk);
-          dma4(real ? (const uint8_t*)ts.sgbase : (const uint8_t*)p.q, (l16 >> 2) & 127);
+          dma4(real ? (const uint8_t*)ts.sgbase : p.kv, (l16 >> 2) & 127);
         }
       } else if constexpr (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
         constexpr int imm = (k & 3) * kMainRowBytes;
