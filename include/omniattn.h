@@ -48,8 +48,12 @@ enum {
   OMNIATTN_EUNSUPPORTED = -2, /* dtype / head count / dims not supported      */
   OMNIATTN_EWORKSPACE = -3,   /* workspace missing or too small               */
   OMNIATTN_EHIP = -4,         /* a HIP call failed; see omniattn_last_hip_error */
-  OMNIATTN_ENOMEM = -5        /* host allocation failed                       */
+  OMNIATTN_ENOMEM = -5,       /* host allocation failed                       */
+  OMNIATTN_ESCRATCH = -6      /* plan too large for omniattn_decode_static    */
 };
+
+/* Size of the library-owned device buffer omniattn_decode_static works in. */
+#define OMNIATTN_STATIC_SCRATCH_BYTES (40u << 20)
 
 /* Statement of one decode problem.  Fixed by the plan; the tensors come later. */
 typedef struct {
@@ -169,6 +173,24 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
                           const float* kv_scales, const int32_t* page_table, void* out,
                           float* lse, void* workspace, size_t workspace_bytes, void* hip_stream,
                           void* ev_begin, void* ev_main_end, void* ev_end);
+
+/*
+ * For callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation,
+ * same kernels and same results as omniattn_decode, but the partial rows of split
+ * sequences go to a buffer of OMNIATTN_STATIC_SCRATCH_BYTES (40 MiB) that is part of the
+ * library's device image; every GPU the library runs on holds it until the process ends.
+ * The call allocates nothing and does not synchronise.  A plan whose
+ * omniattn_plan_workspace_bytes() exceeds the buffer is refused with OMNIATTN_ESCRATCH
+ * (nothing is launched).  All calls on one GPU share that GPU's buffer: two calls that
+ * overlap in time on one GPU (different streams) race; calls on one stream are ordered.
+ * Nothing in the buffer has to start at zero: every partial row is written by the main
+ * kernel before the merge reads it.
+ */
+int omniattn_decode_static(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
+                           const float* kv_scales, const int32_t* page_table, void* out,
+                           float* lse, void* hip_stream);
+size_t omniattn_static_scratch_bytes(void);
 
 /*
  * Physically compressed cache of a compressed layer.  Section 3.2.1 keeps only the

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     omniattn_plan_host,
     omniattn_decode,
     omniattn_decode_timed,
+    omniattn_decode_static,
+    omniattn_static_scratch_bytes,
     omniattn_ring_pages,
     omniattn_ring_slot,
     omniattn_ring_append,

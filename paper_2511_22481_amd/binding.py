@@ -69,6 +69,10 @@ def load_library():
     lib.omniattn_decode.argtypes = [P, P, P, P, P, P, P, P, ctypes.c_size_t, P]
     lib.omniattn_decode_timed.restype = ctypes.c_int
     lib.omniattn_decode_timed.argtypes = [P, P, P, P, P, P, P, P, ctypes.c_size_t, P, P, P, P]
+    lib.omniattn_decode_static.restype = ctypes.c_int
+    lib.omniattn_decode_static.argtypes = [P, P, P, P, P, P, P, P]
+    lib.omniattn_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.omniattn_static_scratch_bytes.argtypes = []
     lib.omniattn_ring_pages.restype = ctypes.c_int32
     lib.omniattn_ring_pages.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.omniattn_ring_slot.restype = ctypes.c_int32
@@ -195,6 +199,21 @@ def omniattn_decode_timed(plan, q, kv_cache, kv_scales, page_table, out, lse, wo
         plan.handle, _ptr(q), _ptr(kv_cache), _ptr(kv_scales), _ptr(page_table), _ptr(out),
         _ptr(lse), _ptr(workspace), ws_bytes, ctypes.c_void_p(stream.cuda_stream),
         ev_begin, ev_main_end, ev_end))
+
+
+def omniattn_decode_static(plan, q, kv_cache, kv_scales, page_table, out, lse, stream=None):
+    """omniattn_decode without a workspace argument: partial rows go to the library's own
+    device buffer (omniattn_static_scratch_bytes() bytes); nothing is allocated."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(load_library().omniattn_decode_static(
+        plan.handle, _ptr(q), _ptr(kv_cache), _ptr(kv_scales), _ptr(page_table), _ptr(out),
+        _ptr(lse), ctypes.c_void_p(stream.cuda_stream)))
+
+
+def omniattn_static_scratch_bytes():
+    return int(load_library().omniattn_static_scratch_bytes())
 
 
 def omniattn_ring_pages(sink, window):

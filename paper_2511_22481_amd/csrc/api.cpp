@@ -22,6 +22,8 @@ struct omniattn_plan_s {
   CombineItem* d_combine = nullptr;
 };
 
+static __device__ __align__(256) unsigned char scratch[OMNIATTN_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_hip_error;
@@ -43,12 +45,24 @@ constexpr int kMaxDevices = 64;
 std::mutex g_init_mutex;
 bool g_init_done[kMaxDevices] = {};
 
+// Workspace of omniattn_decode_static: partial rows of split sequences and their lse.
+// Every device the library runs on holds its own copy of this array until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// address kernels and copies use is the per-device pointer taken once in init_device.
+constexpr size_t kStaticScratchBytes = OMNIATTN_STATIC_SCRATCH_BYTES;
+void* g_scratch_ptr[kMaxDevices] = {};
+
 int init_device(int dev) {
   if (dev < 0 || dev >= kMaxDevices) return OMNIATTN_EINVAL;
   std::lock_guard<std::mutex> lock(g_init_mutex);
   if (g_init_done[dev]) return OMNIATTN_OK;
   hipError_t e = init_kernels();
   if (e != hipSuccess) return hip_fail(e, "kernel attribute setup");
+  // (the caller made `dev` current: the address is that of this device's copy)
+  void* sp = nullptr;
+  e = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !sp) return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+  g_scratch_ptr[dev] = sp;
   g_init_done[dev] = true;
   return OMNIATTN_OK;
 }
@@ -254,6 +268,20 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   return OMNIATTN_OK;
 }
 
+size_t omniattn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int omniattn_decode_static(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
+                           const float* kv_scales, const int32_t* page_table, void* out, float* lse,
+                           void* hip_stream) {
+  if (!plan || !plan->on_device) return OMNIATTN_EINVAL;
+  if (plan->hp.workspace_bytes > kStaticScratchBytes) return OMNIATTN_ESCRATCH;
+  // the plan was made on plan->device, so that device's scratch address is known
+  void* sp = plan->device >= 0 && plan->device < kMaxDevices ? g_scratch_ptr[plan->device] : nullptr;
+  if (!sp) return OMNIATTN_EINVAL;
+  return omniattn_decode_timed(plan, q, kv_cache, kv_scales, page_table, out, lse, sp, kStaticScratchBytes,
+                               hip_stream, nullptr, nullptr, nullptr);
+}
+
 int32_t omniattn_ring_pages(int32_t sink, int32_t window) {
   if (sink < 0 || window < 0) return -1;
   return ring_pinned_pages(sink) + ring_ring_pages(window);
@@ -300,6 +328,9 @@ const char* omniattn_strerror(int code) {
     case OMNIATTN_EWORKSPACE: return "workspace missing, misaligned or too small";
     case OMNIATTN_EHIP: return "HIP call failed (see omniattn_last_hip_error)";
     case OMNIATTN_ENOMEM: return "out of host memory";
+    case OMNIATTN_ESCRATCH:
+      return "the plan's workspace exceeds the built-in scratch buffer of omniattn_decode_static "
+             "(see omniattn_static_scratch_bytes); use omniattn_decode with a caller-owned workspace";
     default: return "unknown error code";
   }
 }
