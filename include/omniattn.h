@@ -91,16 +91,29 @@ typedef struct omniattn_plan_s omniattn_plan_t; /* opaque, library-owned */
  * lengths L_b >= 0 (the token being decoded is already in the cache and is
  * counted).  Requires ceil(L_b/128) <= max_pages_per_seq.
  *
- * omniattn_plan      also uploads the metadata to the current HIP device
- *                    (synchronously; uses hipMalloc) so that omniattn_decode
- *                    can run.  Work is balanced over that device's CU count.
+ * omniattn_plan      also copies the metadata to the current HIP device so that
+ *                    omniattn_decode can run: device and pinned host buffers are
+ *                    allocated here (hipMalloc, hipHostMalloc), the copy itself is
+ *                    asynchronous on `hip_stream`, and decodes of this plan must be
+ *                    ordered after it (same stream, or an event).  Work is balanced
+ *                    over that device's CU count.
+ * omniattn_plan_update  plans again for new lengths of the same problem (every decode
+ *                    step changes every L_b) into the same object: host work, one
+ *                    asynchronous copy from the plan's pinned buffer and one small
+ *                    kernel on `hip_stream`; nothing is allocated and nothing
+ *                    synchronises unless the new plan needs more metadata than any
+ *                    before it.  The plan must not be in use by a decode on another
+ *                    stream.  The workspace size may change: ask again.  On failure
+ *                    for bad lengths the plan is unchanged.  A plan made by
+ *                    omniattn_plan_host is planned again on the host only.
  * omniattn_plan_host builds the same plan for `num_cus` compute units without
  *                    touching HIP; such a plan can be inspected but
  *                    omniattn_decode on it returns OMNIATTN_EINVAL.
  * On failure *plan_out is set to NULL.
  */
 int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
-                  const int32_t* seq_lens_host);
+                  const int32_t* seq_lens_host, void* hip_stream);
+int omniattn_plan_update(omniattn_plan_t* plan, const int32_t* seq_lens_host, void* hip_stream);
 int omniattn_plan_host(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
                        const int32_t* seq_lens_host, int32_t num_cus);
 void omniattn_plan_destroy(omniattn_plan_t* plan); /* NULL is allowed */
@@ -112,6 +125,7 @@ int32_t omniattn_plan_num_units(const omniattn_plan_t* plan);      /* grid of th
 int32_t omniattn_plan_num_segments(const omniattn_plan_t* plan);
 int32_t omniattn_plan_num_partials(const omniattn_plan_t* plan);   /* partial results the combine kernel merges */
 int32_t omniattn_plan_max_splits(const omniattn_plan_t* plan);     /* most pieces any one sequence was cut into */
+int32_t omniattn_plan_num_splits(const omniattn_plan_t* plan);     /* the same number under its other name */
 int32_t omniattn_plan_tile_tokens(const omniattn_plan_t* plan);    /* KV tokens per tile */
 int32_t omniattn_plan_head_block(const omniattn_plan_t* plan);     /* heads per work unit */
 
@@ -155,7 +169,7 @@ int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t til
  * Slots outside the retained set, and pages not referenced, may hold anything
  * (NaN included) without effect.  Page ids of retained pages must lie in
  * [0, num_pages): the kernel does not check device-side contents.
- * Same plan + same inputs give bitwise identical results (no atomics).
+ * Same plan + same inputs give bitwise identical results (nothing is accumulated atomically).
  */
 int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
                     const float* kv_scales, const int32_t* page_table, void* out,
@@ -203,17 +217,22 @@ size_t omniattn_static_scratch_bytes(void);
  * points need nothing new: the page table simply maps the retained logical pages to
  * these pages, and entries of logical pages that hold no retained token are never
  * read.
+ * Several queries per sequence (q_len = T > 1): the earliest of the T queries keeps W
+ * positions that end T - 1 tokens before the newest one, so the layer must keep the
+ * W + T - 1 most recent tokens.  omniattn_ring_pages and omniattn_ring_slot are functions
+ * of that effective window: pass window + T - 1 to them.  omniattn_ring_append reads q_len
+ * from `prob` and adds T - 1 itself.
  *
  * omniattn_ring_slot   which of the sequence's own pages (0 .. ring_pages-1) holds
  *                      logical page `logical_page` (host, pure function; negative
  *                      arguments give -1).
  * omniattn_ring_append appends one token to every sequence of the batch (device
  *                      work on `hip_stream`, asynchronous, allocates nothing):
- *   prob       batch, max_pages_per_seq, sink, window, kv_dtype are used
+ *   prob       batch, max_pages_per_seq, sink, window, q_len, kv_dtype are used
  *   seq_lens   device int32 [B]: lengths before the call; each is incremented
  *   new_rows   device [B, 576] bf16, or e4m3 bytes for an fp8 cache
  *   new_scales device fp32 [B] for an fp8 cache, else NULL
- *   seq_pages  device int32 [B, omniattn_ring_pages(S, W)]: the pool pages each
+ *   seq_pages  device int32 [B, omniattn_ring_pages(S, W + T - 1)]: the pool pages each
  *              sequence owns (distinct)
  *   kv_cache, kv_scales  the pool, as for omniattn_decode
  *   page_table device int32 [B, max_pages_per_seq]: entry L/128 of row b is written

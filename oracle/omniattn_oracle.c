@@ -151,7 +151,10 @@ int omniattn_oracle(int32_t B, int32_t H, const uint16_t *q, const void *cache,
         double *s = (double *)malloc((size_t)n * sizeof *s);
         double *kv = (double *)malloc((size_t)n * QK_DIM * sizeof *kv);
         if (!idx || !s || !kv) {
-            status = -1;
+            {
+#pragma omp atomic write
+                status = -1;
+            }
             free(idx); free(s); free(kv);
             continue;
         }
@@ -183,7 +186,10 @@ int omniattn_oracle(int32_t B, int32_t H, const uint16_t *q, const void *cache,
             }
         }
         if (bad) {
-            status = -2;
+            {
+#pragma omp atomic write
+                status = -2;
+            }
             free(idx); free(s); free(kv);
             continue;
         }

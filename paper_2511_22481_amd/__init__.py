@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     Problem,
     omniattn_plan,
     omniattn_plan_host,
+    omniattn_plan_update,
     omniattn_decode,
     omniattn_decode_timed,
     omniattn_decode_static,

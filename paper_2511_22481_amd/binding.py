@@ -35,17 +35,22 @@ def lib_path():
 
 
 def load_library():
-    """Load libomniattn.so; build it first only if it does not exist."""
+    """Load libomniattn.so.  A library that is missing, or was not built from the present
+    sources (content hash written by the build after the generated-code check has passed), is
+    built first, through that check; if that is not possible the call raises.  A library
+    older than its sources is never loaded."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
-        from .build import build
+    from .build import build, is_stale
+    if _LIB_PATH == os.path.join(HERE, "libomniattn.so") and is_stale():
         build()
     lib = ctypes.CDLL(_LIB_PATH)
     P = ctypes.c_void_p
     lib.omniattn_plan.restype = ctypes.c_int
-    lib.omniattn_plan.argtypes = [ctypes.POINTER(P), ctypes.POINTER(Problem), P]
+    lib.omniattn_plan.argtypes = [ctypes.POINTER(P), ctypes.POINTER(Problem), P, P]
+    lib.omniattn_plan_update.restype = ctypes.c_int
+    lib.omniattn_plan_update.argtypes = [P, P, P]
     lib.omniattn_plan_host.restype = ctypes.c_int
     lib.omniattn_plan_host.argtypes = [ctypes.POINTER(P), ctypes.POINTER(Problem), P, ctypes.c_int32]
     lib.omniattn_plan_destroy.restype = None
@@ -54,8 +59,8 @@ def load_library():
     lib.omniattn_plan_workspace_bytes.argtypes = [P]
     lib.omniattn_plan_retained_tokens.restype = ctypes.c_int64
     lib.omniattn_plan_retained_tokens.argtypes = [P]
-    for name in ("num_units", "num_segments", "num_partials", "max_splits", "tile_tokens",
-                 "head_block"):
+    for name in ("num_units", "num_segments", "num_partials", "max_splits", "num_splits",
+                 "tile_tokens", "head_block"):
         f = getattr(lib, "omniattn_plan_" + name)
         f.restype = ctypes.c_int32
         f.argtypes = [P]
@@ -126,6 +131,7 @@ class Plan:
     num_segments = property(lambda self: self._get("num_segments"))
     num_partials = property(lambda self: self._get("num_partials"))
     max_splits = property(lambda self: self._get("max_splits"))
+    num_splits = property(lambda self: self._get("num_splits"))
     tile_tokens = property(lambda self: self._get("tile_tokens"))
     head_block = property(lambda self: self._get("head_block"))
 
@@ -157,12 +163,31 @@ def _lens_array(seq_lens):
     return (ctypes.c_int32 * max(len(lens), 1))(*lens)
 
 
-def omniattn_plan(seq_lens, **problem_fields):
-    """Plan on the current HIP device.  seq_lens: host sequence of B ints."""
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        if not torch.cuda.is_available():
+            return ctypes.c_void_p(None)  # no GPU: the library itself reports that
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def omniattn_plan(seq_lens, stream=None, **problem_fields):
+    """Plan on the current HIP device; the metadata copy runs on `stream` (default: torch's
+    current stream).  seq_lens: host sequence of B ints."""
     prob = _problem(**problem_fields)
     h = ctypes.c_void_p()
-    _check(load_library().omniattn_plan(ctypes.byref(h), ctypes.byref(prob), _lens_array(seq_lens)))
+    _check(load_library().omniattn_plan(ctypes.byref(h), ctypes.byref(prob), _lens_array(seq_lens),
+                                        _stream_handle(stream)))
     return Plan(h, prob)
+
+
+def omniattn_plan_update(plan, seq_lens, stream=None):
+    """Plan again for new lengths into the same object (no allocation, no synchronisation).
+    seq_lens: host sequence of B ints, or a ctypes int32 array made once by the caller."""
+    lens = seq_lens if isinstance(seq_lens, ctypes.Array) else _lens_array(seq_lens)
+    _check(load_library().omniattn_plan_update(plan.handle, lens, _stream_handle(stream)))
+    return plan
 
 
 def omniattn_plan_host(seq_lens, num_cus=256, **problem_fields):
@@ -216,18 +241,22 @@ def omniattn_static_scratch_bytes():
     return int(load_library().omniattn_static_scratch_bytes())
 
 
-def omniattn_ring_pages(sink, window):
-    """Pages a sequence of a compressed layer owns."""
-    return int(load_library().omniattn_ring_pages(sink, window))
+def _window_union(window, q_len):
+    return window + (q_len - 1 if window > 0 and q_len > 1 else 0)
 
 
-def omniattn_ring_slot(sink, window, logical_page):
+def omniattn_ring_pages(sink, window, q_len=1):
+    """Pages a sequence of a compressed layer owns (q_len queries per decode call)."""
+    return int(load_library().omniattn_ring_pages(sink, _window_union(window, q_len)))
+
+
+def omniattn_ring_slot(sink, window, logical_page, q_len=1):
     """Which of the sequence's own pages holds logical page `logical_page`."""
-    return int(load_library().omniattn_ring_slot(sink, window, logical_page))
+    return int(load_library().omniattn_ring_slot(sink, _window_union(window, q_len), logical_page))
 
 
 def omniattn_ring_append(seq_lens, new_rows, new_scales, seq_pages, kv_cache, kv_scales, page_table,
-                         *, sink, window, stream=None):
+                         *, sink, window, q_len=1, stream=None):
     """Append one token per sequence to a physically compressed cache (all CUDA tensors,
     seq_lens int32 [B] is incremented in place)."""
     import torch
@@ -236,7 +265,7 @@ def omniattn_ring_append(seq_lens, new_rows, new_scales, seq_pages, kv_cache, kv
     fp8 = kv_cache.dtype == torch.float8_e4m3fn
     prob = _problem(batch=int(seq_lens.shape[0]), num_heads=1, max_pages_per_seq=int(page_table.shape[1]),
                     num_pages=int(kv_cache.shape[0]), sink=sink, window=window, softmax_scale=1.0,
-                    kv_dtype=FP8_E4M3 if fp8 else BF16)
+                    kv_dtype=FP8_E4M3 if fp8 else BF16, q_len=q_len)
     _check(load_library().omniattn_ring_append(
         ctypes.byref(prob), _ptr(seq_lens), _ptr(new_rows), _ptr(new_scales), _ptr(seq_pages),
         _ptr(kv_cache), _ptr(kv_scales), _ptr(page_table), ctypes.c_void_p(stream.cuda_stream)))

@@ -1,4 +1,5 @@
 """Compile the HIP library for gfx950 in-tree (paper_2511_22481_amd/libomniattn.so)."""
+import hashlib
 import os
 import subprocess
 
@@ -16,11 +17,25 @@ def hipcc():
     return "hipcc"
 
 
+STAMP = LIB + ".stamp"   # hash of the sources the library was built (and checked) from
+CHECKER = os.path.join(HERE, "check_isa.py")
+
+
+def source_hash():
+    h = hashlib.sha256()
+    for f in sorted(SOURCES + HEADERS):
+        h.update(f.encode())
+        h.update(open(os.path.join(CSRC, f), "rb").read())
+    h.update(open(CHECKER, "rb").read())
+    return h.hexdigest()
+
+
 def is_stale():
-    if not os.path.exists(LIB):
+    """True unless the library exists and was built, and its generated code checked, from
+    exactly the present sources (content hash, so that file times do not matter)."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
         return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
+    return open(STAMP).read().strip() != source_hash()
 
 
 def build(force=True, verbose=False):
@@ -28,6 +43,8 @@ def build(force=True, verbose=False):
     is switched off for the device pass."""
     if not force and not is_stale():
         return LIB
+    if os.path.exists(STAMP):
+        os.remove(STAMP)
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument", "-x", "hip"]
@@ -41,6 +58,8 @@ def build(force=True, verbose=False):
     if res.returncode != 0:
         raise RuntimeError("hipcc failed")
     check_generated_code(verbose)
+    with open(STAMP, "w") as f:     # only a library whose generated code passed the check is stamped
+        f.write(source_hash() + "\n")
     return LIB
 
 

@@ -1,7 +1,9 @@
 // C ABI of the sparse MLA decode library (see include/omniattn.h).
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -16,10 +18,19 @@ struct omniattn_plan_s {
   HostPlan hp;
   bool on_device = false;
   int device = -1;
-  // device copies of the plan metadata (owned)
-  UnitHeader* d_units = nullptr;
-  Segment* d_segs = nullptr;
-  CombineItem* d_combine = nullptr;
+  int num_cus = 0;
+  int xcds = 1;        // work group i runs on XCD i % xcds (measured once per device)
+  // Device copy of the plan metadata (owned): one allocation holding the unit headers, the
+  // segments and the combine items, filled by one asynchronous copy from one of two pinned
+  // host buffers of the same layout (used in turn; an event per buffer says when its last
+  // copy has been read).  omniattn_plan_update reuses all of it when the new plan fits.
+  uint8_t* d_meta = nullptr;
+  size_t meta_cap = 0;
+  uint8_t* h_meta[2] = {nullptr, nullptr};
+  hipEvent_t h_done[2] = {nullptr, nullptr};
+  bool h_busy[2] = {false, false};
+  int h_next = 0;
+  size_t off_segs = 0, off_combine = 0;
 };
 
 static __device__ __align__(256) unsigned char scratch[OMNIATTN_STATIC_SCRATCH_BYTES];
@@ -51,6 +62,7 @@ bool g_init_done[kMaxDevices] = {};
 // address kernels and copies use is the per-device pointer taken once in init_device.
 constexpr size_t kStaticScratchBytes = OMNIATTN_STATIC_SCRATCH_BYTES;
 void* g_scratch_ptr[kMaxDevices] = {};
+int g_xcds[kMaxDevices] = {};
 
 int init_device(int dev) {
   if (dev < 0 || dev >= kMaxDevices) return OMNIATTN_EINVAL;
@@ -63,45 +75,106 @@ int init_device(int dev) {
   e = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
   if (e != hipSuccess || !sp) return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
   g_scratch_ptr[dev] = sp;
+  int xcds = 1;
+  e = probe_xcds(&xcds);
+  if (e != hipSuccess) return hip_fail(e, "XCD probe");
+  g_xcds[dev] = xcds;
   g_init_done[dev] = true;
   return OMNIATTN_OK;
 }
 
 void free_device(omniattn_plan_s* pl) {
-  if (pl->d_units) (void)hipFree(pl->d_units);
-  if (pl->d_segs) (void)hipFree(pl->d_segs);
-  if (pl->d_combine) (void)hipFree(pl->d_combine);
-  pl->d_units = nullptr;
-  pl->d_segs = nullptr;
-  pl->d_combine = nullptr;
+  if (pl->d_meta) (void)hipFree(pl->d_meta);
+  for (int i = 0; i < 2; ++i) {
+    if (pl->h_meta[i]) (void)hipHostFree(pl->h_meta[i]);
+    if (pl->h_done[i]) (void)hipEventDestroy(pl->h_done[i]);
+    pl->h_meta[i] = nullptr;
+    pl->h_done[i] = nullptr;
+    pl->h_busy[i] = false;
+  }
+  pl->d_meta = nullptr;
+  pl->meta_cap = 0;
+}
+
+int build_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t* seq_lens, int num_cus) {
+  try {
+    return build_host_plan(hp, prob, seq_lens, num_cus);
+  } catch (const std::bad_alloc&) {
+    return OMNIATTN_ENOMEM;
+  } catch (...) {
+    return OMNIATTN_EINVAL;
+  }
 }
 
 int make_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob, const int32_t* seq_lens,
               int num_cus) {
   omniattn_plan_s* pl = new (std::nothrow) omniattn_plan_s();
   if (!pl) return OMNIATTN_ENOMEM;
-  int rc;
-  try {
-    rc = build_host_plan(pl->hp, *prob, seq_lens, num_cus);
-  } catch (const std::bad_alloc&) {
-    rc = OMNIATTN_ENOMEM;
-  } catch (...) {
-    rc = OMNIATTN_EINVAL;
-  }
+  const int rc = build_plan(pl->hp, *prob, seq_lens, num_cus);
   if (rc != OMNIATTN_OK) {
     delete pl;
     return rc;
   }
+  pl->num_cus = num_cus;
   *plan_out = pl;
   return OMNIATTN_OK;
 }
 
-template <class T>
-int upload(T** dst, const std::vector<T>& src) {
-  *dst = nullptr;
-  if (src.empty()) return OMNIATTN_OK;
-  OA_HIP(hipMalloc((void**)dst, src.size() * sizeof(T)));
-  OA_HIP(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
+
+// Copies the host plan's metadata to the device on `stream` without synchronising.  Device
+// and pinned buffers are allocated on the first call and again only when a plan outgrows them.
+int upload_plan(omniattn_plan_s* pl, hipStream_t stream) {
+  const HostPlan& hp = pl->hp;
+  const size_t n_units = hp.unit_seg.size() - 1, n_segs = hp.segs.size(), n_items = hp.combine.size();
+  pl->off_segs = align16(n_units * sizeof(UnitHeader));
+  pl->off_combine = pl->off_segs + align16(n_segs * sizeof(DevSegment));
+  const size_t bytes = pl->off_combine + align16(n_items * sizeof(CombineItem));
+  if (bytes > pl->meta_cap) {
+    // (rare: a plan larger than any before it; freeing waits for the device)
+    const size_t cap = bytes + bytes / 2 + 4096;
+    if (pl->d_meta) (void)hipFree(pl->d_meta);
+    pl->d_meta = nullptr;
+    pl->meta_cap = 0;
+    for (int i = 0; i < 2; ++i) {
+      if (pl->h_meta[i]) (void)hipHostFree(pl->h_meta[i]);
+      pl->h_meta[i] = nullptr;
+      pl->h_busy[i] = false;
+      OA_HIP(hipHostMalloc((void**)&pl->h_meta[i], cap, hipHostMallocDefault));
+      if (!pl->h_done[i]) OA_HIP(hipEventCreateWithFlags(&pl->h_done[i], hipEventDisableTiming));
+    }
+    OA_HIP(hipMalloc((void**)&pl->d_meta, cap));
+    pl->meta_cap = cap;
+  }
+  const int hi = pl->h_next;
+  pl->h_next ^= 1;
+  if (pl->h_busy[hi]) OA_HIP(hipEventSynchronize(pl->h_done[hi]));  // its previous copy has been read
+  uint8_t* h = pl->h_meta[hi];
+  // The kernels read a segment's partial slots where the planner's record has the unit and tile count.
+  std::vector<int32_t> item_of_slot((size_t)hp.n_slots, -1);
+  for (size_t i = 0; i < n_items; ++i)
+    for (int k = 0; k < hp.combine[i].nslots; ++k) item_of_slot[hp.combine[i].slot0 + k] = (int32_t)i;
+  auto dev_seg = [&](size_t i) {
+    const Segment& g = hp.segs[i];
+    DevSegment d{g.b, g.hb, g.tile_lo, g.tile_hi, g.slot, 0, g.L, 0};
+    if (g.slot >= 0) {
+      const CombineItem& it = hp.combine[item_of_slot[g.slot]];
+      d.slot0 = it.slot0;
+      d.nslots = it.nslots;
+    }
+    return d;
+  };
+  UnitHeader* hu = (UnitHeader*)h;
+  DevSegment* hs = (DevSegment*)(h + pl->off_segs);
+  for (size_t i = 0; i < n_segs; ++i) hs[i] = dev_seg(i);
+  for (size_t u = 0; u < n_units; ++u) {
+    hu[u] = UnitHeader{hp.unit_seg[u], hp.unit_seg[u + 1], 0, 0, DevSegment{}};
+    if (hu[u].seg_lo < hu[u].seg_hi) hu[u].first = hs[hu[u].seg_lo];
+  }
+  if (n_items) std::memcpy(h + pl->off_combine, hp.combine.data(), n_items * sizeof(CombineItem));
+  OA_HIP(hipMemcpyAsync(pl->d_meta, h, bytes, hipMemcpyHostToDevice, stream));
+  OA_HIP(hipEventRecord(pl->h_done[hi], stream));
+  pl->h_busy[hi] = true;
   return OMNIATTN_OK;
 }
 
@@ -118,7 +191,7 @@ int omniattn_plan_host(omniattn_plan_t** plan_out, const omniattn_problem_t* pro
 }
 
 int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
-                  const int32_t* seq_lens_host) {
+                  const int32_t* seq_lens_host, void* hip_stream) {
   if (!plan_out) return OMNIATTN_EINVAL;
   *plan_out = nullptr;
   if (!prob || !seq_lens_host) return OMNIATTN_EINVAL;
@@ -133,18 +206,12 @@ int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
   rc = make_plan(&pl, prob, seq_lens_host, cus > 0 ? cus : 256);
   if (rc != OMNIATTN_OK) return rc;
   pl->device = dev;
+  pl->xcds = g_xcds[dev] > 0 ? g_xcds[dev] : 1;
   try {
-    std::vector<UnitHeader> hdr(pl->hp.unit_seg.size() - 1);
-    for (size_t u = 0; u + 1 < pl->hp.unit_seg.size(); ++u) {
-      hdr[u] = UnitHeader{pl->hp.unit_seg[u], pl->hp.unit_seg[u + 1], 0, 0, Segment{}};
-      if (hdr[u].seg_lo < hdr[u].seg_hi) hdr[u].first = pl->hp.segs[hdr[u].seg_lo];
-    }
-    rc = upload(&pl->d_units, hdr);
+    rc = upload_plan(pl, (hipStream_t)hip_stream);
   } catch (const std::bad_alloc&) {
     rc = OMNIATTN_ENOMEM;
   }
-  if (rc == OMNIATTN_OK) rc = upload(&pl->d_segs, pl->hp.segs);
-  if (rc == OMNIATTN_OK) rc = upload(&pl->d_combine, pl->hp.combine);
   if (rc != OMNIATTN_OK) {
     free_device(pl);
     delete pl;
@@ -153,6 +220,31 @@ int omniattn_plan(omniattn_plan_t** plan_out, const omniattn_problem_t* prob,
   pl->on_device = true;
   *plan_out = pl;
   return OMNIATTN_OK;
+}
+
+int omniattn_plan_update(omniattn_plan_t* plan, const int32_t* seq_lens_host, void* hip_stream) {
+  if (!plan || !seq_lens_host) return OMNIATTN_EINVAL;
+  const bool host_only = plan->device < 0;  // made by omniattn_plan_host: nothing to copy
+  if (!host_only) {
+    if (!plan->on_device) return OMNIATTN_EINVAL;
+    int dev = -1;
+    OA_HIP(hipGetDevice(&dev));
+    if (dev != plan->device) return OMNIATTN_EINVAL;
+  }
+  // Planned into a scratch object first: a rejected length leaves the plan as it was.
+  HostPlan next;
+  const omniattn_problem_t prob = plan->hp.prob;
+  int rc = build_plan(next, prob, seq_lens_host, plan->num_cus);
+  if (rc != OMNIATTN_OK) return rc;
+  plan->hp = std::move(next);
+  if (host_only) return OMNIATTN_OK;
+  try {
+    rc = upload_plan(plan, (hipStream_t)hip_stream);
+  } catch (const std::bad_alloc&) {
+    rc = OMNIATTN_ENOMEM;
+  }
+  if (rc != OMNIATTN_OK) plan->on_device = false;  // its device copy is no longer whole
+  return rc;
 }
 
 void omniattn_plan_destroy(omniattn_plan_t* plan) {
@@ -175,6 +267,7 @@ int32_t omniattn_plan_num_segments(const omniattn_plan_t* plan) {
 }
 int32_t omniattn_plan_num_partials(const omniattn_plan_t* plan) { return plan ? plan->hp.n_slots : 0; }
 int32_t omniattn_plan_max_splits(const omniattn_plan_t* plan) { return plan ? plan->hp.max_splits : 0; }
+int32_t omniattn_plan_num_splits(const omniattn_plan_t* plan) { return omniattn_plan_max_splits(plan); }
 int32_t omniattn_plan_tile_tokens(const omniattn_plan_t*) { return kTile; }
 int32_t omniattn_plan_head_block(const omniattn_plan_t* plan) { return plan ? plan->hp.head_block : 0; }
 
@@ -232,8 +325,9 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   dp.lse = lse;
   dp.part_lse = (float*)workspace;
   dp.part_o = workspace ? (char*)workspace + hp.part_rows_offset : nullptr;
-  dp.units = plan->d_units;
-  dp.segs = plan->d_segs;
+  dp.units = (const UnitHeader*)plan->d_meta;
+  dp.segs = (const DevSegment*)(plan->d_meta + plan->off_segs);
+  dp.xcds = plan->xcds;
   dp.H = hp.heads_total;
   dp.Hq = hp.prob.num_heads;
   dp.T = hp.q_len;
@@ -254,7 +348,7 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
 
   if (!hp.combine.empty()) {
     CombineParams cp;
-    cp.items = plan->d_combine;
+    cp.items = (const CombineItem*)(plan->d_meta + plan->off_combine);
     cp.part_o = dp.part_o;
     cp.part_lse = dp.part_lse;
     cp.out = out;
@@ -312,9 +406,14 @@ int omniattn_ring_append(const omniattn_problem_t* prob, int32_t* seq_lens, cons
   ap.kv_scales = kv_scales;
   ap.page_table = page_table;
   ap.max_pages = prob->max_pages_per_seq;
+  // With several queries per sequence the earliest query's window reaches q_len - 1 tokens
+  // further back: the ring is laid out for the union of the queries' windows.
+  if (prob->q_len < 0 || prob->q_len > 64) return OMNIATTN_EINVAL;
+  const int64_t w_eff = prob->window > 0 ? (int64_t)prob->window + (prob->q_len > 1 ? prob->q_len - 1 : 0) : 0;
+  if (w_eff > INT32_MAX) return OMNIATTN_EINVAL;
   ap.S = prob->sink;
-  ap.W = prob->window;
-  ap.ring_pages = ring_pinned_pages(prob->sink) + ring_ring_pages(prob->window);
+  ap.W = (int)w_eff;
+  ap.ring_pages = ring_pinned_pages(prob->sink) + ring_ring_pages((int)w_eff);
   ap.row_bytes = fp8 ? kQK : kQK * 2;
   OA_HIP(launch_append(ap, prob->batch, (hipStream_t)hip_stream));
   return OMNIATTN_OK;

@@ -169,7 +169,80 @@ __device__ __forceinline__ u32x4 widen8(uint32_t lo, uint32_t hi) {
                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false)),
                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true))};
 }
-constexpr int kXcds = 8;  // accelerator complex dies: work group i runs on XCD i % 8
+
+// The XCD (accelerator complex die) this wave runs on: compute units of one XCD share an L2.
+__device__ __forceinline__ uint32_t xcc_id() {
+  uint32_t id;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+  return id & 15u;
+}
+
+// One head row of one (sequence, head block) that was cut into nslots partial results:
+// out = sum_s w_s O_s with w_s = exp(lse_s - lse), lse = log sum_s exp(lse_s).  One wave per
+// row, 64 lanes x 8 columns.  Partials are taken four at a time, all their loads in flight
+// together, and folded into a running (maximum, sum, row) triple, so any number of partials
+// takes one pass.  hl: the row inside the head block; orow: the row of out / lse.
+template <bool OUT_FP32>
+__device__ __forceinline__ void merge_row(const void* part_o, const float* part_lse, int slot0, int nslots,
+                                          int head_block, int hl, int lane, void* out, float* lse_out, size_t orow) {
+  constexpr int kBatch = 4;
+  float m = -INFINITY, z = 0.f;
+  float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int s0 = 0; s0 < nslots; s0 += kBatch) {
+    float l[kBatch];
+    f32x4 ra[kBatch], rb[kBatch];
+    bf16x8 rh[kBatch];
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const bool ok = s0 + k < nslots;
+      const size_t row = (size_t)(slot0 + (ok ? s0 + k : 0)) * head_block + hl;
+      l[k] = ok ? part_lse[row] : -INFINITY;
+      if constexpr (OUT_FP32) {
+        const f32x4* src = (const f32x4*)((const float*)part_o + row * kV + lane * 8);
+        ra[k] = src[0];
+        rb[k] = src[1];
+      } else {
+        rh[k] = *(const bf16x8*)((const uint16_t*)part_o + row * kV + lane * 8);
+      }
+    }
+    float mb = m;
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) mb = fmaxf(mb, l[k]);
+    if (mb == -INFINITY) continue;  // nothing but empty partials so far
+    const float keep = __expf(m - mb);  // 0 on the first batch (m = -inf)
+    z *= keep;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] *= keep;
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const float w = __expf(l[k] - mb);  // 0 for a slot past the end
+      z += w;
+      if constexpr (OUT_FP32) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          o[c] = fmaf(w, ra[k][c], o[c]);
+          o[4 + c] = fmaf(w, rb[k][c], o[4 + c]);
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[c] = fmaf(w, (float)rh[k][c], o[c]);
+      }
+    }
+    m = mb;
+  }
+  const float inv = z > 0.f ? 1.0f / z : 0.f;
+  if (lane == 0) lse_out[orow] = z > 0.f ? m + __logf(z) : -INFINITY;
+  if constexpr (OUT_FP32) {
+    float* dst = (float*)out + orow * kV + lane * 8;
+    *(f32x4*)dst = f32x4{o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
+    *(f32x4*)(dst + 4) = f32x4{o[4] * inv, o[5] * inv, o[6] * inv, o[7] * inv};
+  } else {
+    bf16x8 v;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = (__bf16)(o[k] * inv);
+    *(bf16x8*)((uint16_t*)out + orow * kV + lane * 8) = v;
+  }
+}
 
 template <int WAVES, bool FP8>
 __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
@@ -199,11 +272,11 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   // plus one for its 32 scales
   constexpr int kDmaPerTile = FP8 ? 6 : kRowsPerWave + kRowsPerWave / 8;
 
-  // Work groups are dealt to the eight XCDs round-robin.  Consecutive work units (the
-  // pieces of one sequence, which read the same Q and neighbouring pages) are mapped to
-  // work groups of one XCD so that they share its L2.
-  const int per_xcd = (p.n_units + kXcds - 1) / kXcds;
-  const int unit = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  // Work groups are dealt to the XCDs round-robin (p.xcds of them, measured on the device).
+  // Consecutive work units (the pieces of one sequence, which read the same Q and exchange
+  // their partial results) are mapped to work groups of one XCD so that they share its L2.
+  const int per_xcd = (p.n_units + p.xcds - 1) / p.xcds;
+  const int unit = ((int)blockIdx.x % p.xcds) * per_xcd + (int)blockIdx.x / p.xcds;
   if (unit >= p.n_units) return;
   // The unit's header (segment range and a copy of its first segment) in three 16-byte
   // loads issued together; the values are wave-uniform and moved to scalar registers.
@@ -211,7 +284,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     return u32x4{(uint32_t)__builtin_amdgcn_readfirstlane(v.x), (uint32_t)__builtin_amdgcn_readfirstlane(v.y),
                  (uint32_t)__builtin_amdgcn_readfirstlane(v.z), (uint32_t)__builtin_amdgcn_readfirstlane(v.w)};
   };
-  static_assert(sizeof(UnitHeader) == 48 && sizeof(Segment) == 32, "header layout");
+  static_assert(sizeof(UnitHeader) == 48 && sizeof(DevSegment) == 32, "header layout");
   const u32x4* hdr = (const u32x4*)(p.units + unit);
   const u32x4 hdr0 = hdr[0], hdr1 = hdr[1], hdr2 = hdr[2];
   const int seg_lo = __builtin_amdgcn_readfirstlane(hdr0.x), seg_hi = __builtin_amdgcn_readfirstlane(hdr0.y);
@@ -228,8 +301,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     }
     sg_a = uniform4(sg_a);
     sg_b = uniform4(sg_b);
-    const Segment sg = {(int32_t)sg_a.x, (int32_t)sg_a.y, (int32_t)sg_a.z, (int32_t)sg_a.w,
-                        (int32_t)sg_b.x, (int32_t)sg_b.y, (int32_t)sg_b.z, (int32_t)sg_b.w};
+    const DevSegment sg = {(int32_t)sg_a.x, (int32_t)sg_a.y, (int32_t)sg_a.z, (int32_t)sg_a.w,
+                           (int32_t)sg_b.x, (int32_t)sg_b.y, (int32_t)sg_b.z, (int32_t)sg_b.w};
     const int L = sg.L;
     const int h0 = sg.hb * p.head_block + wave * kHeadsPerWave;  // wave's first head
     const int lane_s = fresh_lane();
@@ -436,6 +509,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         *LDS_PTR(u32x2, lds_tiles + t * 8) = u32x2{(uint32_t)a | (uint32_t)tile_full(pos0), (uint32_t)(a >> 32)};
       }
     }
+    if (tid == 0) *LDS_PTR(int, lds_flag) = 0;  // the retry vote at the segment's end
     __syncthreads();
     issue_tile(0);
     issue_tile(1);
@@ -833,13 +907,16 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       }
       wait_vm<0>();  // the junk-region loads issued for tiles past the end
 
-      // Did any lane of the work group see a logit too far above its reference?
-      if (tid == 0) *LDS_PTR(int, lds_flag) = 0;
-      __syncthreads();  // also: all reads of the stages are done before they are reused
-      if (attempt == 0 && __any(mt_all > kRefSlack) && (tid & 63) == 0) *LDS_PTR(int, lds_flag) = 1;
-      __syncthreads();
-      if (*LDS_PTR(int, lds_flag) == 0) break;
+      // Did any head of the work group see its largest logit too far from its reference?  Too
+      // far above, the weights could overflow; too far below (possible when the first tile
+      // holds nothing for a query, so that its reference is 0), they underflow and the sum
+      // loses its digits or vanishes.  Either way the segment is run again with the exact
+      // maximum as reference.  (The flag was cleared before this segment's first barrier.)
       const float m2 = fmaxf(mt_all, __shfl_xor(mt_all, 32));
+      const bool off = m2 > kRefSlack || (m2 < -kRefSlack && m2 != -INFINITY);
+      if (attempt == 0 && __any(off) && (tid & 63) == 0) *LDS_PTR(int, lds_flag) = 1;
+      __syncthreads();  // also: all reads of the stages are done before they are reused
+      if (*LDS_PTR(int, lds_flag) == 0) break;
       ref_exact = m2 == -INFINITY ? 0.f : ref + ceilf(m2);
     }
 
@@ -900,11 +977,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   }
 }
 
-// Merge the partial results of one (sequence, head block): out = sum_s w_s O_s with
-// w_s = exp(lse_s - lse), lse = log sum_s exp(lse_s).  One work group per
-// (combine item, group of 4 heads); 64 lanes x 8 columns cover one head row.  Partials
-// are taken four at a time, all their loads in flight together, and folded into a
-// running (maximum, sum, row) triple, so any number of partials takes one pass.
+// Merge the partial results of one (sequence, head block): one work group per
+// (combine item, group of 4 heads), one wave per head row (see merge_row).
 // One instance per output type: with both in one kernel the registers of the fp32 path
 // cost the bf16 path a third of its waves in flight, and this kernel lives on those.
 template <bool OUT_FP32>
@@ -913,67 +987,14 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
   const int hl = blockIdx.y * 4 + (threadIdx.x >> 6);
   const int head = it.hb * p.head_block + hl;
   if (hl >= p.head_block || head >= p.H) return;
-  const int lane = threadIdx.x & 63;
-  constexpr int kBatch = 4;
-  float m = -INFINITY, z = 0.f;
-  float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int s0 = 0; s0 < it.nslots; s0 += kBatch) {
-    float l[kBatch];
-    f32x4 ra[kBatch], rb[kBatch];
-    bf16x8 rh[kBatch];
-#pragma unroll
-    for (int k = 0; k < kBatch; ++k) {
-      const bool ok = s0 + k < it.nslots;
-      const size_t row = (size_t)(it.slot0 + (ok ? s0 + k : 0)) * p.head_block + hl;
-      l[k] = ok ? p.part_lse[row] : -INFINITY;
-      if constexpr (OUT_FP32) {
-        const f32x4* src = (const f32x4*)((const float*)p.part_o + row * kV + lane * 8);
-        ra[k] = src[0];
-        rb[k] = src[1];
-      } else {
-        rh[k] = *(const bf16x8*)((const uint16_t*)p.part_o + row * kV + lane * 8);
-      }
-    }
-    float mb = m;
-#pragma unroll
-    for (int k = 0; k < kBatch; ++k) mb = fmaxf(mb, l[k]);
-    if (mb == -INFINITY) continue;  // nothing but empty partials so far
-    const float keep = __expf(m - mb);  // 0 on the first batch (m = -inf)
-    z *= keep;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) o[c] *= keep;
-#pragma unroll
-    for (int k = 0; k < kBatch; ++k) {
-      const float w = __expf(l[k] - mb);  // 0 for a slot past the end
-      z += w;
-      if constexpr (OUT_FP32) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          o[c] = fmaf(w, ra[k][c], o[c]);
-          o[4 + c] = fmaf(w, rb[k][c], o[4 + c]);
-        }
-      } else {
-#pragma unroll
-        for (int c = 0; c < 8; ++c) o[c] = fmaf(w, (float)rh[k][c], o[c]);
-      }
-    }
-    m = mb;
-  }
-  const float inv = z > 0.f ? 1.0f / z : 0.f;
-  const size_t orow = (size_t)it.b * p.H + head;
-  if (lane == 0) p.lse[orow] = z > 0.f ? m + __logf(z) : -INFINITY;
-  if constexpr (OUT_FP32) {
-    float* dst = (float*)p.out + orow * kV + lane * 8;
-    *(f32x4*)dst = f32x4{o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
-    *(f32x4*)(dst + 4) = f32x4{o[4] * inv, o[5] * inv, o[6] * inv, o[7] * inv};
-  } else {
-    bf16x8 v;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = (__bf16)(o[k] * inv);
-    *(bf16x8*)((uint16_t*)p.out + orow * kV + lane * 8) = v;
-  }
+  merge_row<OUT_FP32>(p.part_o, p.part_lse, it.slot0, it.nslots, p.head_block, hl, threadIdx.x & 63, p.out, p.lse,
+                      (size_t)it.b * p.H + head);
 }
 
+// One work group of 64 threads per probe block: the XCD the block runs on.
+__global__ void xcd_probe_kernel(int* out) {
+  if (threadIdx.x == 0) out[blockIdx.x] = (int)xcc_id();
+}
 
 template <int WAVES, bool FP8>
 static hipError_t set_lds_attr() {
@@ -991,8 +1012,9 @@ hipError_t init_kernels() {
 hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream) {
   if (n_units <= 0) return hipSuccess;
   if (waves != 4) return hipErrorInvalidValue;
+  if (p.xcds < 1) return hipErrorInvalidValue;
   // the grid is rounded up to a multiple of the XCD count (see the unit mapping in the kernel)
-  dim3 grid(((n_units + kXcds - 1) / kXcds) * kXcds), block(waves * 64);
+  dim3 grid(((n_units + p.xcds - 1) / p.xcds) * p.xcds), block(waves * 64);
   if (!fp8) hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, kLdsBytes, stream, p);
   else hipLaunchKernelGGL((decode_kernel<4, true>), grid, block, kLdsBytes, stream, p);
   return hipGetLastError();
@@ -1004,6 +1026,27 @@ hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t strea
   if (p.out_fp32) hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, stream, p);
   else hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, stream, p);
   return hipGetLastError();
+}
+
+hipError_t probe_xcds(int* n_xcds) {
+  constexpr int kBlocks = 64;
+  *n_xcds = 1;
+  int* d = nullptr;
+  hipError_t e = hipMalloc((void**)&d, kBlocks * sizeof(int));
+  if (e != hipSuccess) return e;
+  int h[kBlocks];
+  hipLaunchKernelGGL(xcd_probe_kernel, dim3(kBlocks), dim3(64), 0, 0, d);
+  e = hipGetLastError();
+  if (e == hipSuccess) e = hipMemcpy(h, d, sizeof(h), hipMemcpyDeviceToHost);
+  (void)hipFree(d);
+  if (e != hipSuccess) return e;
+  int n = 0;
+  for (int i = 0; i < kBlocks; ++i) n = h[i] + 1 > n ? h[i] + 1 : n;
+  if (n < 1 || n > 16) return hipSuccess;
+  for (int i = 0; i < kBlocks; ++i)
+    if (h[i] != i % n) return hipSuccess;  // not round-robin: the kernel then does not remap
+  *n_xcds = n;
+  return hipSuccess;
 }
 
 }  // namespace omniattn

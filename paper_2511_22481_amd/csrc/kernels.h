@@ -7,6 +7,21 @@
 
 namespace omniattn {
 
+// A segment as the kernels read it: the planner's record with the two fields the device has
+// no use for (work unit, tile count of the sequence) replaced by the partial slots of the
+// segment's (sequence, head block): [slot0, slot0 + nslots) when it was cut, else nslots = 0.
+struct DevSegment {
+  int32_t b, hb, tile_lo, tile_hi, slot, slot0, L, nslots;
+};
+static_assert(sizeof(DevSegment) == sizeof(Segment), "same size as the planner's record");
+
+// What a work unit reads first: its range of segments and a copy of the first of them,
+// so that the kernel's first dependent load already yields a segment.
+struct UnitHeader {
+  int32_t seg_lo, seg_hi, pad0, pad1;
+  DevSegment first;
+};
+
 struct DecodeParams {
   const uint16_t* q;
   const uint8_t* kv;
@@ -17,7 +32,8 @@ struct DecodeParams {
   void* part_o;     // [n_slots, head_block, 512] in the output type (bf16 or fp32)
   float* part_lse;  // [n_slots, head_block]
   const UnitHeader* units;
-  const Segment* segs;
+  const DevSegment* segs;
+  int xcds;     // work group i runs on XCD i % xcds (1: no remapping)
   int H;        // rows of q per sequence: heads x queries
   int Hq, T;    // heads per query, queries per sequence (T >= 1)
   int Wu;       // W + T - 1: window of the union of the queries' kept sets
@@ -51,5 +67,8 @@ hipError_t init_kernels();
 // waves must be 4; grid = number of work units.
 hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream);
 hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t stream);
+// Number of XCDs if work groups are dealt to them round-robin (work group i on XCD i % n),
+// measured by a probe kernel on the current device; 1 if the pattern does not hold.
+hipError_t probe_xcds(int* n_xcds);
 
 }  // namespace omniattn

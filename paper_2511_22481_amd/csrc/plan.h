@@ -70,13 +70,6 @@ struct Segment {
   int32_t b, hb, tile_lo, tile_hi, slot, unit, L, ntiles;
 };
 
-// What a work unit reads first: its range of segments and a copy of the first of them,
-// so that the kernel's first dependent load already yields a segment.
-struct UnitHeader {
-  int32_t seg_lo, seg_hi, pad0, pad1;
-  Segment first;
-};
-
 // One (sequence, head block) whose tiles were cut into several segments.
 struct CombineItem {
   int32_t b, hb, slot0, nslots;

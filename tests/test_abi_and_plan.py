@@ -125,6 +125,37 @@ def test_split_hint_cuts_every_sequence():
     assert p.max_splits == 1 and p.num_partials == 0 and p.workspace_bytes == 0
 
 
+def test_plan_update_equals_fresh_plan():
+    """Planning again into an existing object (every decode step changes every length) gives
+    the plan a fresh omniattn_plan_host call gives, segment by segment."""
+    rng = random.Random(11)
+    for _ in range(25):
+        B = rng.randint(1, 12)
+        S = rng.choice([0, 64, 128])
+        W = rng.choice([0, 512, 2048, 9000])
+        H = rng.choice([16, 128, 160])
+        cus = rng.choice([8, 256])
+        hint = rng.choice([0, 0, 3])
+        lens = [rng.randint(1, 6000) for _ in range(B)]
+        mp = 64
+        kw = dict(num_cus=cus, batch=B, num_heads=H, max_pages_per_seq=mp, num_pages=B * mp,
+                  sink=S, window=W, softmax_scale=0.1, num_splits_hint=hint)
+        plan = oa.omniattn_plan_host(lens, **kw)
+        for step in range(4):
+            lens = [min(L + rng.choice([1, 1, 1, 200]), mp * 128) for L in lens]
+            oa.omniattn_plan_update(plan, lens)
+            fresh = oa.omniattn_plan_host(lens, **kw)
+            assert plan.segments() == fresh.segments()
+            for name in ("num_units", "num_partials", "max_splits", "num_splits", "retained_tokens",
+                         "workspace_bytes"):
+                assert getattr(plan, name) == getattr(fresh, name), name
+        # a rejected length leaves the plan as it was
+        before = plan.segments()
+        with pytest.raises(oa.OmniAttnError):
+            oa.omniattn_plan_update(plan, [mp * 128 + 1] * B)
+        assert plan.segments() == before
+
+
 def test_argument_validation():
     ok = dict(batch=1, num_heads=16, max_pages_per_seq=4, num_pages=4, sink=1, window=1,
               softmax_scale=1.0)

@@ -269,11 +269,14 @@ def test_fp8_reference_overflow_retry():
     parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what="fp8 overflow retry")
 
 
-# --------------------------------------------------- full-size workloads, sampled outputs ---
+# ------------------------------------------------------------------ full-size workloads ---
 @pytest.mark.parametrize("name,n_pairs", [("r1_b64_32k", 64), ("dense_b32_4k", 48), ("fp8_b32_128k", 32),
-                                          ("mixed_b256", 64)])
-def test_full_size_workload_sampled(name, n_pairs):
-    """The launch configuration bench.py times; outputs sampled per (sequence, head)."""
+                                          ("mixed_b256", 64), ("r1_b64_32k_dense", 24)])
+def test_full_size_workload(name, n_pairs):
+    """The launch configuration bench.py times.  Every (sequence, head) row of the output is
+    compared with the oracle (a fault tied to one work unit or one XCD cannot hide between
+    samples); only the uncompressed layer r1_b64_32k_dense, 2.1 M retained tokens per head, is
+    sampled.  Then the stress variant of the same shape (logits of order one), sampled."""
     cfg = get_config(name)
     inp = make_inputs(cfg, device="cuda")
     out, lse, plan = parity.run_gpu(inp)
@@ -281,10 +284,39 @@ def test_full_size_workload_sampled(name, n_pairs):
     out2, lse2, _ = parity.run_gpu(inp, plan=plan)
     assert torch.equal(out, out2) and torch.equal(lse, lse2)
     pairs = sample_pairs(inp.batch, inp.heads, n_pairs, seed=cfg.seed)
-    e = parity.assert_parity(inp, out, lse, pairs=pairs, row_rel_l2=2e-2, what=name)
+    full = name != "r1_b64_32k_dense"
+    e = parity.assert_parity(inp, out, lse, pairs=None if full else pairs, row_rel_l2=2e-2, what=name)
+    print(f"{name}: {'all' if full else len(pairs)} rows {e}")
     if name == "dense_b32_4k":            # S + W >= L: equals full attention, every token counted once
         assert plan.retained_tokens == cfg.batch * cfg.ctx
     # the stress variant of the same shape: logits of order one
     inp.q = (inp.q.float() * (24.0 * np.sqrt(192.0) * (1.0 if cfg.kv_dtype == "bf16" else 1 / 24))).to(torch.bfloat16)
     out, lse, _ = parity.run_gpu(inp, plan=plan)
     parity.assert_parity(inp, out, lse, pairs=pairs, row_rel_l2=2e-2, what=name + " stress")
+
+
+@pytest.mark.gpu
+def test_plan_update_then_decode_matches_oracle():
+    """A decode step lengthens every sequence: the plan is refreshed in place on the launch
+    stream (no allocation, no synchronisation) and the next decode must match the oracle for
+    the new lengths.  The copy of step k+1 is queued while the decode of step k may still run."""
+    lens = [1900, 4095, 33, 2600, 127, 5000]
+    grown = [[L + k for L in lens] for k in (0, 1, 2, 130)]
+    inp = make_custom(batch=len(lens), heads=128, seq_lens=grown[-1], sink=128, window=2048, seed=91, device="cuda")
+    plan = oa.omniattn_plan(grown[0], batch=inp.batch, num_heads=inp.heads, max_pages_per_seq=inp.max_pages,
+                            num_pages=inp.num_pages, sink=inp.sink, window=inp.window,
+                            softmax_scale=inp.softmax_scale, kv_dtype=oa.BF16, out_dtype=oa.BF16)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    outs = []
+    for k, cur in enumerate(grown):
+        if k:
+            oa.omniattn_plan_update(plan, cur)
+        assert plan.workspace_bytes <= ws.numel()
+        out = torch.empty((inp.batch, inp.heads, 512), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((inp.batch, inp.heads), dtype=torch.float32, device="cuda")
+        oa.omniattn_decode(plan, inp.q, inp.kv_cache, inp.kv_scales, inp.page_table, out, lse, ws)
+        outs.append((out, lse))
+    torch.cuda.synchronize()
+    for cur, (out, lse) in zip(grown, outs):
+        inp.seq_lens_host = list(cur)
+        parity.assert_parity(inp, out, lse, what=f"after update to {cur}")

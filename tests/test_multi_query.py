@@ -59,7 +59,7 @@ def _check(inp, out, lse, T, what, row_rel_l2=1e-2):
                                         inp.seq_lens_host, inp.sink, inp.window, inp.softmax_scale,
                                         kv_dtype=inp.kv_dtype, q_len=T)
     e = parity.errors(out, lse, ref_o, ref_l)
-    scale = max(1.0, float(np.nanmax(np.abs(ref_o))))
+    scale = parity.abs_scale(out, ref_o)
     assert e["max_abs"] <= parity.MAX_ABS * scale and e["rel_l2"] <= parity.REL_L2[inp.kv_dtype], (what, e)
     assert e["lse_abs"] <= parity.LSE_ABS and e["worst_row_rel_l2"] <= row_rel_l2, (what, e)
 
@@ -99,3 +99,26 @@ def test_one_query_is_the_plain_decode():
                             inp.seq_lens_host, inp.sink, inp.window, inp.softmax_scale)
     torch.cuda.synchronize()
     assert torch.equal(out.reshape(B, 32, 512), out1) and torch.equal(lse.reshape(B, 32), lse1)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_first_tile_empty_for_a_query_with_very_negative_logits(kv_dtype):
+    """S = 0, W = 32, 33 queries, L = 128: the tiles cover positions 64 .. 127, and the latest
+    query keeps nothing of the first tile.  Its softmax reference then starts at 0, while every
+    logit is about -144 (2^-208 in the kernel's base-2 weights): without a second pass against
+    the true maximum the sum underflows to nothing.  The early queries keep only the first tile."""
+    T, H, S, W, L = 33, 4, 0, 32, 128
+    kv_std = 0.02 if kv_dtype == "bf16" else 0.5
+    inp = parity.to_device(make_custom(2, T * H, [L, L + 7], S, W, seed=123, q_std=0.02, kv_std=kv_std,
+                                       softmax_scale=1.0, kv_dtype=kv_dtype))
+    if kv_dtype == "bf16":
+        inp.q[..., 0] = -12.0
+        inp.kv_cache[..., 0] = 12.0
+    else:                                    # every row's scale 1/64; code 384 is the value 6
+        inp.q[..., 0] = -24.0
+        inp.kv_cache[..., 0] = torch.tensor(384.0).to(torch.float8_e4m3fn)
+        inp.kv_scales[...] = 1.0 / 64.0
+    out, lse, _ = _run(inp, T, H)
+    assert torch.isfinite(lse).all() and float(lse.max()) < -100.0
+    _check(inp, out, lse, T, "very negative logits", row_rel_l2=2e-2)

@@ -42,6 +42,50 @@ def test_ring_mapping_never_loses_a_retained_token(S, W):
     assert oa.omniattn_ring_slot(S, W, -1) == -1 and oa.omniattn_ring_pages(-1, 3) == -1
 
 
+@pytest.mark.parametrize("T", [2, 3, 64])
+@pytest.mark.parametrize("S,W", [(0, 128), (0, 1), (100, 130), (128, 256), (64, 127), (5, 129)])
+def test_ring_mapping_with_several_queries(S, W, T):
+    """T queries per decode call: query t sees a sequence of length L - (T - 1 - t) and keeps
+    its own sinks and window, so the earliest one reaches T - 1 tokens further back.  The ring
+    sized for q_len = T must hold every position any of the T queries keeps, at every length."""
+    n_pages = oa.omniattn_ring_pages(S, W, q_len=T)
+    assert n_pages == oa.omniattn_ring_pages(S, W + T - 1)
+    holds = {}
+    for L_before in range(0, 7 * PAGE + 11):
+        lp = L_before // PAGE
+        slot = oa.omniattn_ring_slot(S, W, lp, q_len=T)
+        assert 0 <= slot < n_pages
+        if L_before % PAGE == 0:
+            holds[slot] = lp
+        assert holds[slot] == lp
+        L = L_before + 1
+        if L < T:
+            continue
+        for t in (0, T // 2, T - 1):
+            Lq = L - (T - 1 - t)
+            # every page of the two retained ranges (both ends and one position per page between)
+            lo = max(Lq - W, 0)
+            js = set(range(0, min(S, Lq), PAGE)) | set(range(lo, Lq, PAGE)) | {min(S, Lq) - 1, lo, Lq - 1}
+            for j in js:
+                if retained(j, Lq, S, W):
+                    assert holds.get(oa.omniattn_ring_slot(S, W, j // PAGE, q_len=T)) == j // PAGE, (L, t, j)
+
+
+def test_ring_sized_for_one_query_loses_tokens_of_three():
+    """The case that motivates the rule above: S = 0, W = 128, three queries, L = 257.  Query 0
+    keeps token 127, whose page a ring laid out for one query has already handed on."""
+    S, W, T, L = 0, 128, 3, 257
+    lost = []
+    for sized_for in (1, T):
+        holds = {}
+        for pos in range(L):
+            if pos % PAGE == 0:
+                holds[oa.omniattn_ring_slot(S, W, pos // PAGE, q_len=sized_for)] = pos // PAGE
+        j = L - (T - 1) - W      # first position query 0 keeps
+        lost.append(holds.get(oa.omniattn_ring_slot(S, W, j // PAGE, q_len=sized_for)) != j // PAGE)
+    assert lost == [True, False]
+
+
 def _decode(q, cache, scales, table, lens, S, W, scale):
     out, lse, _ = oa.decode(q, cache, scales, table, lens, S, W, scale)
     torch.cuda.synchronize()
