@@ -9,14 +9,21 @@ resident in HBM; the plan is built once before the timed region.  To keep the
 (q, cache, page table) sets whose touched KV together exceeds the 256 MB
 last-level cache.
 
+Timing: after --warmup steps, --batches batches of --steps steps each are timed back
+to back, each batch between two events on the launch stream; ms_per_step is the
+MEDIAN batch divided by --steps (the spread over the batches is reported too).
+
 Prints ONE JSON line: retained KV tokens/s, ms per step, the roofline of the
-dominant kernel (live HIP-event timing on the launch stream), and the fp64 CPU
-oracle timed on a bounded sample of the same workload.
+dominant kernel (live HIP-event timing on the launch stream) and of the whole
+step, the fp64 CPU oracle timed on a bounded sample of the same workload, and the
+parity of the timed configuration against that oracle on a few output rows.
 """
 import argparse
 import ctypes
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -27,8 +34,22 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 WORKLOAD = "r1_b64_32k"
 # HBM bytes per launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file (profiles/decode_kernel_r1_b64_32k_hbm_counters.md), scaled by what the same
-# counters read for a 1 GiB device copy.  To be re-taken whenever the kernel changes.
-MEASURED_TRAFFIC_BYTES = {"r1_b64_32k": 170_635_500 + 36_044_800}
+# counters read for a 1 GiB device copy.  The figure belongs to one version of the kernel
+# source: it is reported only while the source's hash is the one the counters were taken
+# with, and as null from the next kernel change on until they are taken again.
+MEASURED_TRAFFIC = {
+    "r1_b64_32k": {"bytes": 170_635_500 + 36_044_800,
+                   "kernel_sha256": "0" * 64},
+}
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2511_22481_amd", "csrc", "decode_kernels.hip")
+
+
+def measured_traffic(workload):
+    rec = MEASURED_TRAFFIC.get(workload)
+    if not rec:
+        return None
+    sha = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+    return rec["bytes"] if sha == rec["kernel_sha256"] else None
 
 
 def algorithmic_bytes(retained_tokens, batch, heads, kv_dtype):
@@ -43,6 +64,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--batches", type=int, default=10,
+                    help="timed batches of --steps steps; the median batch is reported")
     ap.add_argument("--sets", type=int, default=3, help="independent input sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default=WORKLOAD)
@@ -84,7 +107,24 @@ def main():
     t_plan = time.perf_counter()
     for _ in range(5):
         make_plan(sets[0]).destroy()
-    plan_ms = (time.perf_counter() - t_plan) / 5 * 1e3
+    plan_create_ms = (time.perf_counter() - t_plan) / 5 * 1e3
+    # What a decode step pays: planning again for new lengths into an existing plan (host work
+    # and one asynchronous copy on the launch stream; nothing allocated, nothing synchronised).
+    # Timed on a plan of its own, alternating between the workload's lengths and lengths one
+    # token shorter (the page tables have no room for longer ones), from length arrays the
+    # caller keeps (as a serving loop would).
+    spare = make_plan(sets[0])
+    lens_next = (ctypes.c_int32 * sets[0].batch)(*[max(int(L) - 1, 1) for L in sets[0].seq_lens_host])
+    lens_now = (ctypes.c_int32 * sets[0].batch)(*[int(L) for L in sets[0].seq_lens_host])
+    for _ in range(5):
+        oa.omniattn_plan_update(spare, lens_next)
+    torch.cuda.synchronize()
+    t_plan = time.perf_counter()
+    for i in range(50):
+        oa.omniattn_plan_update(spare, lens_next if i % 2 == 0 else lens_now)
+    plan_ms = (time.perf_counter() - t_plan) / 50 * 1e3
+    torch.cuda.synchronize()
+    spare.destroy()
     plan = plans[0]
     out = torch.empty((inp0.batch, inp0.heads, 512), dtype=torch.bfloat16, device=dev)
     lse = torch.empty((inp0.batch, inp0.heads), dtype=torch.float32, device=dev)
@@ -107,19 +147,22 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    # whole-step timing: K steps between two events on the launch stream
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
+    # whole-step timing: batches of K steps, each between two events on the launch stream
+    n_batches = max(1, args.batches)
+    evs_t = [torch.cuda.Event(enable_timing=True) for _ in range(n_batches + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    e0.record(stream)
-    for i in range(args.steps):
-        step(i)
-    e1.record(stream)
+    evs_t[0].record(stream)
+    k = 0
+    for bi in range(n_batches):
+        for _ in range(args.steps):
+            step(k)
+            k += 1
+        evs_t[bi + 1].record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    ev_ms = e0.elapsed_time(e1)
-    ms_per_step = max(ev_ms, 0.0) / args.steps
+    batch_ms = [evs_t[i].elapsed_time(evs_t[i + 1]) / args.steps for i in range(n_batches)]
+    ms_per_step = statistics.median(batch_ms)
 
     # dominant kernel alone: HIP events recorded by the library on the launch stream
     # right before and after the main kernel of every step (torch's events only see
@@ -161,6 +204,7 @@ def main():
     value = retained / (ms_per_step * 1e-3)
     kern_ms = main_ms
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    roof_ms = alg_bytes / (HBM_PEAK_GBPS * 1e9) * 1e3   # the step's algorithmic bytes at the HBM peak
 
     result = {
         "metric": "sparse MLA decode: retained KV tokens/s + HBM GB/s, B=64 ctx 32k",
@@ -186,7 +230,11 @@ def main():
             "partials": plan.num_partials,
             "head_block": plan.head_block,
             "plan_ms": plan_ms,
-            "wall_ms_per_step": wall_ms / args.steps,
+            "plan_create_ms": plan_create_ms,
+            "batches": n_batches,
+            "ms_per_step_min": min(batch_ms),
+            "ms_per_step_max": max(batch_ms),
+            "wall_ms_per_step": wall_ms / (args.steps * n_batches),
         },
         "roofline": {
             "bound": "hbm",
@@ -195,9 +243,13 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            "traffic": measured_traffic(cfg.name),
             "kernel_ms": kern_ms,
             "combine_ms": combine_ms,
+            # the whole step (main kernel + combine + what lies between them) against the same
+            # roofline: time the algorithmic bytes take at the HBM peak / median step time
+            "roof_ms": roof_ms,
+            "frac_step": roof_ms / ms_per_step,
         },
     }
 
@@ -222,6 +274,26 @@ def main():
         except AttributeError:
             cores = os.cpu_count()
         cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        # parity of the timed configuration on a few output rows, against the same oracle
+        # (after the timed region; the rows are recomputed by the library on this input set)
+        import numpy as np
+        oa.omniattn_decode(plans[0], s0.q, s0.kv_cache, s0.kv_scales, s0.page_table, out, lse, ws, stream)
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(0)
+        pairs = sorted({(int(rng.integers(s0.batch)), int(rng.integers(s0.heads))) for _ in range(16)}
+                       | {(0, 0), (s0.batch - 1, s0.heads - 1)})
+        ref_o, ref_l = oracle.oracle_decode(host[0], host[1], host[2], host[3], s0.seq_lens_host, s0.sink,
+                                            s0.window, s0.softmax_scale, kv_dtype=s0.kv_dtype, pairs=pairs)
+        idx = torch.as_tensor(np.asarray(pairs), dtype=torch.long, device=dev)
+        g_o = out[idx[:, 0], idx[:, 1]].float().cpu().numpy().astype(np.float64)
+        g_l = lse[idx[:, 0], idx[:, 1]].cpu().numpy().astype(np.float64)
+        result["parity"] = {
+            "rows": len(pairs),
+            "max_abs": float(np.abs(g_o - ref_o).max()),
+            "rel_l2": float(np.linalg.norm(g_o - ref_o) / np.linalg.norm(ref_o)),
+            "lse_max_abs": float(np.abs(g_l - ref_l).max()),
+            "against": "fp64 oracle, same input bits",
+        }
         result["cpu_baseline"] = {
             "value": toks / dt,
             "unit": "retained KV tokens/s",

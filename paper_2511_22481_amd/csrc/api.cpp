@@ -172,7 +172,7 @@ int upload_plan(omniattn_plan_s* pl, hipStream_t stream) {
     if (hu[u].seg_lo < hu[u].seg_hi) hu[u].first = hs[hu[u].seg_lo];
   }
   if (n_items) std::memcpy(h + pl->off_combine, hp.combine.data(), n_items * sizeof(CombineItem));
-  OA_HIP(hipMemcpyAsync(pl->d_meta, h, bytes, hipMemcpyHostToDevice, stream));
+  OA_HIP(launch_copy16(pl->d_meta, h, bytes, stream));
   OA_HIP(hipEventRecord(pl->h_done[hi], stream));
   pl->h_busy[hi] = true;
   return OMNIATTN_OK;

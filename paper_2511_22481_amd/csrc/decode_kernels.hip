@@ -991,6 +991,14 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
                       (size_t)it.b * p.H + head);
 }
 
+// Plan metadata from the plan's pinned host buffer (mapped into the device's address space)
+// to its device copy, 16 bytes per thread.  A kernel rather than a copy command: a launch
+// costs the host a few microseconds, a small asynchronous copy several times that.
+__global__ __launch_bounds__(256) void copy16_kernel(u32x4* dst, const u32x4* src, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
 // One work group of 64 threads per probe block: the XCD the block runs on.
 __global__ void xcd_probe_kernel(int* out) {
   if (threadIdx.x == 0) out[blockIdx.x] = (int)xcc_id();
@@ -1025,6 +1033,13 @@ hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t strea
   dim3 grid(n_items, (p.head_block + 3) / 4), block(256);
   if (p.out_fp32) hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, stream, p);
   else hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy16(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream) {
+  const int n = (int)((bytes + 15) / 16);
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(copy16_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, (u32x4*)dst, (const u32x4*)src_pinned, n);
   return hipGetLastError();
 }
 

@@ -67,6 +67,9 @@ hipError_t init_kernels();
 // waves must be 4; grid = number of work units.
 hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream);
 hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t stream);
+// Copies `bytes` (rounded up to 16; both buffers are that large) from pinned host memory to
+// device memory with a small kernel on `stream`.
+hipError_t launch_copy16(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream);
 // Number of XCDs if work groups are dealt to them round-robin (work group i on XCD i % n),
 // measured by a probe kernel on the current device; 1 if the pattern does not hold.
 hipError_t probe_xcds(int* n_xcds);
