@@ -6,8 +6,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libomniattn.so")
-SOURCES = ["decode_kernels.hip", "append_kernels.hip", "api.cpp", "plan.cpp"]
-HEADERS = ["kernels.h", "plan.h", os.path.join("..", "..", "include", "omniattn.h")]
+SOURCES = ["decode_kernels.hip", "decode_fp8_kernel.hip", "append_kernels.hip", "api.cpp", "plan.cpp"]
+HEADERS = ["kernels.h", "plan.h", "decode_common.h", os.path.join("..", "..", "include", "omniattn.h")]
 
 
 def hipcc():
@@ -69,16 +69,18 @@ def check_generated_code(verbose=False):
     result too early."""
     import tempfile
     from .check_isa import check
+    problems = []
     with tempfile.TemporaryDirectory() as tmp:
-        out = os.path.join(tmp, "decode_kernels.s")
-        cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++20",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wno-unused-command-line-argument", "--cuda-device-only", "-S", "-x", "hip",
-               os.path.join(CSRC, "decode_kernels.hip"), "-o", out]
-        res = subprocess.run(cmd, capture_output=True, text=True)
-        if res.returncode != 0:
-            raise RuntimeError("hipcc -S failed:\n" + res.stderr[-2000:])
-        problems = check(open(out).read())
+        for src, kernel in (("decode_kernels.hip", "decode_kernel"), ("decode_fp8_kernel.hip", "decode_fp8_kernel")):
+            out = os.path.join(tmp, src + ".s")
+            cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++20",
+                   "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                   "-Wno-unused-command-line-argument", "--cuda-device-only", "-S", "-x", "hip",
+                   os.path.join(CSRC, src), "-o", out]
+            res = subprocess.run(cmd, capture_output=True, text=True)
+            if res.returncode != 0:
+                raise RuntimeError("hipcc -S failed:\n" + res.stderr[-2000:])
+            problems += check(open(out).read(), kernel)
     if problems:
         raise RuntimeError("generated code reads MFMA results too early:\n" + "\n".join(problems[:20]))
     if verbose:

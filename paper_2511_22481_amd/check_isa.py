@@ -1,9 +1,9 @@
 """Static check of the generated gfx950 code for hazards the compiler cannot see.
 
-The decode kernel issues its MFMAs from inline assembly, so the compiler's hazard
+The decode kernels issue their MFMAs from inline assembly, so the compiler's hazard
 recognizer does not know that the registers they write are not readable for a
-number of wait states (12 after an 8-pass MFMA for a vector-ALU read, more for a
-memory instruction).  Our own code supplies the `s_nop`s where it reads results;
+number of wait states (12 after an 8-pass MFMA for a vector-ALU read, 20 after a
+16-pass one, more for a memory instruction).  Our own code supplies the `s_nop`s where it reads results;
 this check guards against compiler-inserted code (register moves, spills) that
 touches an MFMA destination too early.  It walks each decode kernel's
 instruction stream in program order, conservatively assuming fall-through, and
@@ -16,6 +16,7 @@ import sys
 VALU_STATES = 12  # vector-ALU read of an 8-pass MFMA result
 MEM_STATES = 19   # memory / LDS / export instruction reading it
 MIN_STATES = VALU_STATES
+EXTRA_16_PASS = 8  # a 16-pass MFMA (the 32x32x64 8-bit one) needs this many more of each
 _MEM_PREFIXES = ("scratch_", "global_", "buffer_", "flat_", "ds_")
 
 _REG_RANGE = re.compile(r"\b([av])\[(\d+):(\d+)\]")
@@ -52,6 +53,7 @@ def check(asm_text, kernel_filter="decode_kernel"):
     # 2. MFMA results read too early
     in_kernel = False
     pending = {}  # register -> wait states elapsed since the MFMA that writes it
+    extra = {}    # register -> additional wait states its MFMA needs (16-pass)
     for lineno, raw in enumerate(asm_text.splitlines(), 1):
         line = raw.split(";")[0].strip()
         if not line:
@@ -68,12 +70,13 @@ def check(asm_text, kernel_filter="decode_kernel"):
             dst = _regs(operands[0])
             srcs = _regs(",".join(operands[1:3]))  # A and B must be readable; C may chain
             for r in srcs:
-                if r in pending and pending[r] < MIN_STATES:
+                if r in pending and pending[r] < MIN_STATES + extra.get(r, 0):
                     problems.append(f"line {lineno}: MFMA reads {r} {pending[r]} states after an MFMA wrote it: {line}")
             for r in list(pending):
                 pending[r] += 1
             for r in dst:
                 pending[r] = 0
+                extra[r] = EXTRA_16_PASS if "32x32x64" in op else 0
             continue
         states = 1
         if op == "s_nop":
@@ -85,13 +88,13 @@ def check(asm_text, kernel_filter="decode_kernel"):
                 op.startswith("ds_read") or op.startswith("ds_bpermute")
             read_text = ",".join(operands[1:]) if writes_first else rest
             for r in _regs(read_text):
-                if r in pending and pending[r] < need:
+                if r in pending and pending[r] < need + extra.get(r, 0):
                     problems.append(f"line {lineno}: {pending[r]} wait states after MFMA write of "
                                     f"{r[0]}{r[1]}: {line}")
             if writes_first:  # overwritten: later uses no longer see the MFMA's result
                 for r in _regs(operands[0]):
                     if r in pending:
-                        if pending[r] < VALU_STATES:
+                        if pending[r] < VALU_STATES + extra.get(r, 0):
                             problems.append(f"line {lineno}: overwrite {pending[r]} wait states after MFMA "
                                             f"write of {r[0]}{r[1]}: {line}")
                         del pending[r]

@@ -69,6 +69,7 @@ int init_device(int dev) {
   std::lock_guard<std::mutex> lock(g_init_mutex);
   if (g_init_done[dev]) return OMNIATTN_OK;
   hipError_t e = init_kernels();
+  if (e == hipSuccess) e = init_fp8_kernel();
   if (e != hipSuccess) return hip_fail(e, "kernel attribute setup");
   // (the caller made `dev` current: the address is that of this device's copy)
   void* sp = nullptr;
@@ -268,7 +269,7 @@ int32_t omniattn_plan_num_segments(const omniattn_plan_t* plan) {
 int32_t omniattn_plan_num_partials(const omniattn_plan_t* plan) { return plan ? plan->hp.n_slots : 0; }
 int32_t omniattn_plan_max_splits(const omniattn_plan_t* plan) { return plan ? plan->hp.max_splits : 0; }
 int32_t omniattn_plan_num_splits(const omniattn_plan_t* plan) { return omniattn_plan_max_splits(plan); }
-int32_t omniattn_plan_tile_tokens(const omniattn_plan_t*) { return kTile; }
+int32_t omniattn_plan_tile_tokens(const omniattn_plan_t* plan) { return plan ? plan->hp.tile : 0; }
 int32_t omniattn_plan_head_block(const omniattn_plan_t* plan) { return plan ? plan->hp.head_block : 0; }
 
 int32_t omniattn_plan_get_segments(const omniattn_plan_t* plan, int32_t* buf, int32_t cap) {
@@ -283,10 +284,10 @@ int32_t omniattn_plan_get_segments(const omniattn_plan_t* plan, int32_t* buf, in
 int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t tile, int32_t* lo,
                              int32_t* hi) {
   if (!plan || !lo || !hi || b < 0 || b >= plan->hp.prob.batch) return OMNIATTN_EINVAL;
-  TileLayout tl = tile_layout(plan->hp.seq_lens[b], plan->hp.prob.sink, plan->hp.window_union);
+  TileLayout tl = tile_layout(plan->hp.seq_lens[b], plan->hp.prob.sink, plan->hp.window_union, plan->hp.tile);
   if (tile < 0 || tile >= tl.count()) return OMNIATTN_EINVAL;
-  *lo = tl.logical(tile) * kTile;
-  *hi = *lo + kTile;
+  *lo = tl.logical(tile) * plan->hp.tile;
+  *hi = *lo + plan->hp.tile;
   return OMNIATTN_OK;
 }
 
@@ -343,7 +344,8 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
   dp.scale_log2 = hp.prob.softmax_scale * 1.4426950408889634f;
   if (dp.scale_log2 == 0.f) dp.scale_log2 = 1e-30f;
   if (ev_begin) OA_HIP(hipEventRecord((hipEvent_t)ev_begin, stream));
-  OA_HIP(launch_decode(dp, hp.waves, fp8, (int)hp.unit_seg.size() - 1, stream));
+  if (fp8) OA_HIP(launch_decode_fp8(dp, (int)hp.unit_seg.size() - 1, stream));
+  else OA_HIP(launch_decode(dp, hp.waves, (int)hp.unit_seg.size() - 1, stream));
   if (ev_main_end) OA_HIP(hipEventRecord((hipEvent_t)ev_main_end, stream));
 
   if (!hp.combine.empty()) {

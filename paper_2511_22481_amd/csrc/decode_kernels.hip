@@ -24,22 +24,9 @@
 #include <type_traits>
 #include <utility>
 
-#include "kernels.h"
+#include "decode_common.h"
 
 namespace omniattn {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-#define LDS_PTR(T, byte_off) ((__attribute__((address_space(3))) T*)(uintptr_t)(byte_off))
 
 constexpr int kRowBytes = kQK * 2;             // one token row in global memory (bf16)
 constexpr int kChunksPerRow = kRowBytes / 16;  // 72
@@ -81,10 +68,6 @@ __device__ __forceinline__ uint32_t lds_chunk(int r, int c) {
 constexpr int kOutRowBytes = 1024 + 16;
 constexpr int kOutWaveBytes = kHeadsPerWave * kOutRowBytes;  // 33,280; x4 waves fits the stages
 
-__device__ __forceinline__ bool retained(int j, int L, int S, int W) {
-  return j < L && (j < S || j >= L - W);
-}
-
 // Register files.  At one wave per SIMD a wave has 256 vector registers and 256
 // accumulation registers.  The O^T tile (512 columns x 32 heads, fp32) fills the
 // accumulation file exactly; Q (144 registers), S, P and operand fragments live in
@@ -112,46 +95,6 @@ __device__ __forceinline__ void settle_o(f32x16 (&acc)[kV / 32]) {
                  "+a"(acc[12]), "+a"(acc[13]), "+a"(acc[14]), "+a"(acc[15]));
 }
 
-// Direct global->LDS load of 16 bytes per lane: lane l's bytes land at LDS address
-// M0 + IMM + 16 l and are read from base + off + IMM (base wave-uniform, off per lane;
-// the instruction's immediate offset applies to both sides).  Written as assembly so
-// that the compiler does not treat it as a store that may alias every later LDS read
-// and drain the whole prefetch before the first read of another stage; completion is
-// awaited explicitly (wait_vm) before the barrier that publishes the tile.
-// M0 carries the LDS base.  Nothing else in these kernels uses M0 (no indirect register
-// addressing, no GWS, no compiler-issued LDS-DMA), so it is simply overwritten.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void dma_set_lds_base(uint32_t lds_base) {
-  const uint32_t slds = __builtin_amdgcn_readfirstlane(lds_base);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(slds) : "m0");
-}
-template <int IMM>
-__device__ __forceinline__ void dma16(const uint8_t* base, uint32_t off) {
-  // wave-uniform by construction; make that visible to the register allocator
-  const uint64_t b = (uint64_t)(uintptr_t)base;
-  const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
-  const uint32_t b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-  const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
-  // nt: cache rows are read once per work unit; marking them as streaming keeps them from
-  // pushing Q (shared by the units of a sequence) and the partial results out of the caches
-  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2 nt" : : "v"(off), "s"(sbase), "n"(IMM) : "m0");
-}
-// 4 bytes per lane: lane l's dword lands at M0 + 4 l.
-__device__ __forceinline__ void dma4(const uint8_t* base, uint32_t off) {
-  const uint64_t b = (uint64_t)(uintptr_t)base;
-  const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
-  const uint32_t b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-  const uint64_t sbase = ((uint64_t)b_hi << 32) | b_lo;
-  asm volatile("global_load_lds_dword %0, %1" : : "v"(off), "s"(sbase) : "m0");
-}
-#pragma clang diagnostic pop
-// Wait until at most N of this wave's vector-memory operations are outstanding.
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 // Softmax reference.  exp2(x - r) is evaluated against a per-head reference r that is
 // fixed for a whole segment (the maximum of the segment's first tile), not against a
 // running maximum: softmax is invariant to r, so the only requirement is that exp2
@@ -168,13 +111,6 @@ __device__ __forceinline__ u32x4 widen8(uint32_t lo, uint32_t hi) {
                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true)),
                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false)),
                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true))};
-}
-
-// The XCD (accelerator complex die) this wave runs on: compute units of one XCD share an L2.
-__device__ __forceinline__ uint32_t xcc_id() {
-  uint32_t id;
-  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
-  return id & 15u;
 }
 
 // One head row of one (sequence, head block) that was cut into nslots partial results:
@@ -1013,18 +949,16 @@ static hipError_t set_lds_attr() {
 hipError_t init_kernels() {
   hipError_t e;
   if ((e = set_lds_attr<4, false>()) != hipSuccess) return e;
-  if ((e = set_lds_attr<4, true>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
-hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream) {
+hipError_t launch_decode(const DecodeParams& p, int waves, int n_units, hipStream_t stream) {
   if (n_units <= 0) return hipSuccess;
   if (waves != 4) return hipErrorInvalidValue;
   if (p.xcds < 1) return hipErrorInvalidValue;
   // the grid is rounded up to a multiple of the XCD count (see the unit mapping in the kernel)
   dim3 grid(((n_units + p.xcds - 1) / p.xcds) * p.xcds), block(waves * 64);
-  if (!fp8) hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, kLdsBytes, stream, p);
-  else hipLaunchKernelGGL((decode_kernel<4, true>), grid, block, kLdsBytes, stream, p);
+  hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, kLdsBytes, stream, p);
   return hipGetLastError();
 }
 

@@ -64,8 +64,11 @@ hipError_t launch_append(const AppendParams& p, int batch, hipStream_t stream);
 
 // One-time per-process kernel attribute setup (large dynamic LDS).
 hipError_t init_kernels();
-// waves must be 4; grid = number of work units.
-hipError_t launch_decode(const DecodeParams& p, int waves, bool fp8, int n_units, hipStream_t stream);
+// bf16 cache.  waves must be 4; grid = number of work units.
+hipError_t launch_decode(const DecodeParams& p, int waves, int n_units, hipStream_t stream);
+// fp8 cache: its own kernel (decode_fp8_kernel.hip), tiles of kTileFp8 tokens.
+hipError_t init_fp8_kernel();
+hipError_t launch_decode_fp8(const DecodeParams& p, int n_units, hipStream_t stream);
 hipError_t launch_combine(const CombineParams& p, int n_items, hipStream_t stream);
 // Copies `bytes` (rounded up to 16; both buffers are that large) from pinned host memory to
 // device memory with a small kernel on `stream`.

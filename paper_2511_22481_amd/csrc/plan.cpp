@@ -96,6 +96,7 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
   hp.waves = 4;
   hp.head_block = hp.waves * kHeadsPerWave;
   hp.q_len = q_len;
+  hp.tile = prob.kv_dtype == OMNIATTN_FP8_E4M3 ? kTileFp8 : kTile;
   hp.heads_total = prob.num_heads * q_len;
   // Several causal queries: query t keeps [0, S) and the W positions ending at its own token.
   // Over all queries that is [0, S) and (for W > 0) the W + q_len - 1 positions ending at L:
@@ -117,7 +118,7 @@ int build_host_plan(HostPlan& hp, const omniattn_problem_t& prob, const int32_t*
   // land on one XCD (see the unit mapping in the kernel) and share its L2
   for (int b = 0; b < prob.batch; ++b)
     for (int hb = 0; hb < hp.n_hb; ++hb) {
-      int n = tile_layout(seq_lens[b], prob.sink, hp.window_union).count();
+      int n = tile_layout(seq_lens[b], prob.sink, hp.window_union, hp.tile).count();
       items.push_back({b, hb, n});
       total_cost += n + kSegFixedCost;
     }

@@ -22,7 +22,8 @@
 
 namespace omniattn {
 
-constexpr int kTile = 32;    // KV tokens per tile (divides the 128-token page)
+constexpr int kTile = 32;    // KV tokens per tile of a bf16 cache (divides the 128-token page)
+constexpr int kTileFp8 = 64; // KV tokens per tile of an fp8 cache: the fp8 matrix instruction contracts 64 tokens
 constexpr int kQK = OMNIATTN_QK_DIM;
 constexpr int kV = OMNIATTN_V_DIM;
 constexpr int kPage = OMNIATTN_PAGE;
@@ -38,15 +39,15 @@ struct TileLayout {
   OA_HD int logical(int i) const { return i < ns ? i : w0 + (i - ns); }
 };
 
-OA_HD inline TileLayout tile_layout(int L, int S, int W) {
+OA_HD inline TileLayout tile_layout(int L, int S, int W, int tile = kTile) {
   TileLayout t;
   if (L < 0) L = 0;
   int sink_end = S < L ? S : L;                 // sink range [0, sink_end)
   bool has_recent = W > 0 && L > 0;             // recent range [max(L - W, 0), L)
   int win_lo = L - W > 0 ? L - W : 0;
-  t.ns = (sink_end + kTile - 1) / kTile;
-  t.w1 = has_recent ? (L + kTile - 1) / kTile : 0;
-  int w0 = has_recent ? win_lo / kTile : 0;
+  t.ns = (sink_end + tile - 1) / tile;
+  t.w1 = has_recent ? (L + tile - 1) / tile : 0;
+  int w0 = has_recent ? win_lo / tile : 0;
   t.w0 = w0 > t.ns ? w0 : t.ns;                 // tiles shared with the sink range count once
   if (t.w0 > t.w1) t.w0 = t.w1;
   return t;
@@ -81,6 +82,7 @@ struct HostPlan {
   int waves = 0;        // waves per work group; each owns 32 heads
   int head_block = 0;   // heads per work unit = 32 * waves
   int n_hb = 0;         // head blocks per sequence
+  int tile = kTile;       // KV tokens per tile (kTile, or kTileFp8 for an fp8 cache)
   int q_len = 1;          // queries per sequence
   int heads_total = 0;    // q_len * num_heads rows of q per sequence ("virtual heads")
   int window_union = 0;   // window + q_len - 1: the union of the queries' windows ends at L

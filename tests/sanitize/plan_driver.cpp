@@ -27,7 +27,7 @@ static int check(const HostPlan& hp) {
   }
   for (int b = 0; b < hp.prob.batch; ++b)
     for (int hb = 0; hb < hp.n_hb; ++hb)
-      if (next[(size_t)b * hp.n_hb + hb] != tile_layout(hp.seq_lens[b], hp.prob.sink, hp.window_union).count()) return 5;
+      if (next[(size_t)b * hp.n_hb + hb] != tile_layout(hp.seq_lens[b], hp.prob.sink, hp.window_union, hp.tile).count()) return 5;
   for (char c : slot_seen)
     if (!c) return 6;
   for (const CombineItem& it : hp.combine)
