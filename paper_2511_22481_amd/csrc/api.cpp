@@ -358,6 +358,7 @@ int omniattn_decode_timed(const omniattn_plan_t* plan, const void* q, const void
     cp.H = dp.H;
     cp.head_block = hp.head_block;
     cp.out_fp32 = dp.out_fp32;
+    cp.n_items = (int)hp.combine.size();
     OA_HIP(launch_combine(cp, (int)hp.combine.size(), stream));
   }
   if (ev_end) OA_HIP(hipEventRecord((hipEvent_t)ev_end, stream));

@@ -1,11 +1,12 @@
 // gfx950 kernels for sparse MLA decode over the OmniAttn retained set
-// (paper section 3.2.1: softmax(q K_M^T * scale) V_M with M = sinks + recents).
+// (paper section 3.2.1: softmax(q K_M^T * scale) V_M with M = sinks + recents):
+// the main kernel for a bf16 cache (an fp8 cache has its own, decode_fp8_kernel.hip),
+// the combine kernel and small helpers.
 //
 // Main kernel: one work group per work unit, WAVES waves, one wave per SIMD; each
 // wave owns 32 heads and the full 512-wide output row of those heads.
 //   a3  retained 32-token tiles stream into a ring of four LDS stages by direct
-//       global->LDS 16-byte loads, two tiles ahead of the compute (fp8 cache: the
-//       raw bytes come the same way and are widened to bf16 out of LDS);
+//       global->LDS 16-byte loads, two tiles ahead of the compute;
 //   a4  S^T[token, head] = K_tile . Q^T on 32x32x16 bf16 MFMA, Q held in
 //       registers as the B operand for the whole segment;
 //   a5  positions outside the retained set get -inf (partial tiles only);
@@ -47,14 +48,9 @@ constexpr int kTailRowBytes = 128;
 constexpr int kTailBase = kTile * kMainRowBytes;                      // 32,768
 constexpr int kStageBytes = kTile * (kMainRowBytes + kTailRowBytes);  // 36,864
 constexpr int kStages = 4;
-constexpr int kScaleBytes = 256;  // per-token fp32 scales of one stage (fp8 cache): 32 used, written twice over by a 64-lane direct load
-// fp8 cache: three bf16 stages; the fourth stage's space holds two buffers of raw tile bytes
-constexpr int kRawTileBytes = kTile * kQK;  // 18,432
-static_assert(2 * kRawTileBytes <= kStageBytes, "raw buffers fit the fourth stage");
 constexpr int kTileTabBytes = kMaxSegTiles * 8;  // first global byte of every tile of the segment
 constexpr int kJunkBytes = 4096;  // target of the direct loads issued for tiles that do not exist
-constexpr int kZeroBytes = kQK;    // fp8: a row of zero codes, read in place of rows outside the retained set
-constexpr int kLdsBytes = kStages * (kStageBytes + kScaleBytes) + 16 + kTileTabBytes + kJunkBytes + kZeroBytes;  // 16: retry flag
+constexpr int kLdsBytes = kStages * kStageBytes + 16 + kTileTabBytes + kJunkBytes;  // 16: retry flag
 static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
 __host__ __device__ constexpr int swz_main(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 __host__ __device__ constexpr int swz_tail(int r) { return (r >> 1) & 7; }
@@ -104,14 +100,6 @@ __device__ __forceinline__ void settle_o(f32x16 (&acc)[kV / 32]) {
 // summing a million terms) the work group runs the same segment code a second time
 // with r = that exact maximum, which cannot overflow.
 constexpr float kRefSlack = 64.f;
-
-// Eight e4m3 codes (two dwords) to eight bf16: the conversion is exact, bf16 holds every e4m3 value.
-__device__ __forceinline__ u32x4 widen8(uint32_t lo, uint32_t hi) {
-  return u32x4{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false)),
-               __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true)),
-               __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false)),
-               __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true))};
-}
 
 // One head row of one (sequence, head block) that was cut into nslots partial results:
 // out = sum_s w_s O_s with w_s = exp(lse_s - lse), lse = log sum_s exp(lse_s).  One wave per
@@ -180,15 +168,13 @@ __device__ __forceinline__ void merge_row(const void* part_o, const float* part_
   }
 }
 
-template <int WAVES, bool FP8>
+template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds_raw;  // LDS byte address of stage 0
-  const uint32_t lds_scales = lds0 + kStages * kStageBytes;
-  const uint32_t lds_flag = lds_scales + kStages * kScaleBytes;
+  const uint32_t lds_flag = lds0 + kStages * kStageBytes;
   const uint32_t lds_tiles = lds_flag + 16;
   const uint32_t lds_junk = lds_tiles + kTileTabBytes;
-  const uint32_t lds_zero = lds_junk + kJunkBytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -203,10 +189,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   };
 
   constexpr int kRowsPerWave = kTile / WAVES;                  // 8, 16 or 32
-  // direct loads per wave and tile.  bf16: one per row plus one for the rope parts of 8 rows;
-  // fp8: the tile's 18 KB of codes as 18 pieces dealt round-robin (5 per wave, two of them void)
-  // plus one for its 32 scales
-  constexpr int kDmaPerTile = FP8 ? 6 : kRowsPerWave + kRowsPerWave / 8;
+  // direct loads per wave and tile: one per row plus one for the rope parts of 8 rows
+  constexpr int kDmaPerTile = kRowsPerWave + kRowsPerWave / 8;
 
   // Work groups are dealt to the XCDs round-robin (p.xcds of them, measured on the device).
   // Consecutive work units (the pieces of one sequence, which read the same Q and exchange
@@ -224,9 +208,6 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
   const u32x4* hdr = (const u32x4*)(p.units + unit);
   const u32x4 hdr0 = hdr[0], hdr1 = hdr[1], hdr2 = hdr[2];
   const int seg_lo = __builtin_amdgcn_readfirstlane(hdr0.x), seg_hi = __builtin_amdgcn_readfirstlane(hdr0.y);
-  if constexpr (FP8) {  // published by the first barrier of the first segment
-    if (tid < kZeroBytes / 4) *LDS_PTR(uint32_t, lds_zero + tid * 4) = 0u;
-  }
 
   for (int si = seg_lo; si < seg_hi; ++si) {
     u32x4 sg_a = hdr1, sg_b = hdr2;
@@ -255,26 +236,23 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     const int sink_end = p.S < L0 ? p.S : L0;
 
     auto tile_pos = [&](int it) { return tl.logical(sg.tile_lo + it) * kTile; };
-    // ring position of a tile's bf16 stage (three stages when the fourth holds raw fp8 tiles)
+    // ring position of a tile's stage
     // (unsigned: a signed remainder could be negative as far as the compiler knows, and it
     // then refuses to fold constant offsets into the LDS instructions built on these addresses)
-    auto stage_of = [](int it) -> uint32_t { return FP8 ? (uint32_t)it % 3u : (uint32_t)it & (kStages - 1); };
-    const uint32_t lds_rawbuf = lds0 + 3 * kStageBytes;
+    auto stage_of = [](int it) -> uint32_t { return (uint32_t)it & (kStages - 1); };
     auto tile_full = [&](int pos0) {
       return (pos0 + kTile <= sink_end) || (pos0 >= L - p.W && pos0 + kTile <= L0);
     };
     // ---- tile loader: wave w fills rows [w * kRowsPerWave, ...) of stage it & 3 ----
     // A tile is fetched by kDmaPerTile direct-load instructions per wave.  Exactly that
     // many are issued for every tile index, also for tiles past the segment's end and for
-    // tiles filled through registers (partial tiles, fp8): those point at a junk region.
+    // tiles filled through registers (partial tiles): those point at a junk region.
     // The count of loads in flight per tile is therefore a constant, which is what the
     // vmcnt-based wait_tile relies on, and the loop needs no branch per load.
     struct TileSrc {
       const uint8_t* gbase;   // first byte of the tile's rows in the cache (placeholder loads: page 0 of the cache)
       uint32_t lmain, ltail;  // LDS destinations of row 0 (main part, tail part)
       uint32_t mstride, tstride;  // 1024 / 128, or 0 for the junk target
-      const float* sgbase;    // fp8: the tile's 32 scales in global memory
-      uint32_t lscale;        // fp8: their LDS slot
     };
     auto prep_tile_e = [&](int it, uint32_t e_lo, uint32_t e_hi) -> TileSrc {
       TileSrc ts;
@@ -283,8 +261,6 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       ts.gbase = p.kv;
       ts.lmain = ts.ltail = lds_junk;
       ts.mstride = ts.tstride = 0;
-      ts.sgbase = nullptr;
-      ts.lscale = lds_junk;
       if (it >= n_tiles) return ts;
       // table entry: first global byte of the tile's rows; bit 0 = every position retained
       const bool full = e_lo & 1;
@@ -292,59 +268,24 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       const int stage = stage_of(it);
       const uint32_t lbase = lds0 + stage * kStageBytes;
       const int row_w0 = wave * kRowsPerWave;
-      if constexpr (!FP8) {
-        if (full) {
-          ts.gbase = gbase;
-          ts.lmain = lbase;
-          ts.ltail = lbase + kTailBase;
-          ts.mstride = kMainRowBytes;
-          ts.tstride = kTailRowBytes;
-        } else {
-          // partial tile: rows outside the retained set are zero-filled, never loaded
-          // (their contents are unspecified and 0 * NaN would poison the PV product)
-          const int pos0 = tile_pos(it);
-#pragma unroll 1
-          for (int ci = lane; ci < kRowsPerWave * kChunksPerRow; ci += 64) {
-            const int r = ci / kChunksPerRow;
-            const int c = ci - r * kChunksPerRow;
-            const int row = row_w0 + r;
-            u32x4 v = {0, 0, 0, 0};
-            if (retained(pos0 + row, L, p.S, p.Wu)) v = *(const u32x4*)(gbase + row * kRowBytes + (c << 4));
-            *LDS_PTR(u32x4, lbase + lds_chunk(row, c)) = v;
-          }
-        }
+      if (full) {
+        ts.gbase = gbase;
+        ts.lmain = lbase;
+        ts.ltail = lbase + kTailBase;
+        ts.mstride = kMainRowBytes;
+        ts.tstride = kTailRowBytes;
       } else {
-        // fp8 rows: 36 chunks of 16 codes; every code is widened exactly to bf16 and the
-        // token's fp32 scale is kept aside: it multiplies the logit (after QK^T) and the
-        // softmax weight (before PV), both in fp32, so dequantisation adds no rounding.
-        // Tiles 0 and 1 are filled here, through registers; from tile 2 on the raw bytes
-        // and the scales come by direct loads two tiles ahead (dma_piece) and are widened
-        // out of LDS while the tile before is being multiplied (convert pass in the loop).
-        const float* sbase = p.kv_scales + (gbase - p.kv) / kQK;
-        if (it >= 2) {
-          ts.gbase = gbase;
-          ts.lmain = lds_rawbuf + (it & 1) * kRawTileBytes;
-          ts.mstride = 1024;
-          ts.sgbase = sbase;
-          ts.lscale = lds_scales + (it & 3) * kScaleBytes;  // four slots: tile it-2's was last read two barriers ago
-          return ts;
-        }
+        // partial tile: rows outside the retained set are zero-filled, never loaded
+        // (their contents are unspecified and 0 * NaN would poison the PV product)
         const int pos0 = tile_pos(it);
-        constexpr int n_chunks = kTile * (kQK / 16);  // 1152
 #pragma unroll 1
-        for (int ci = tid; ci < n_chunks; ci += WAVES * 64) {
-          const int row = ci / (kQK / 16);
-          const int cc = ci - row * (kQK / 16);
-          u32x4 raw = {0, 0, 0, 0};
-          if (full || retained(pos0 + row, L, p.S, p.Wu)) raw = *(const u32x4*)(gbase + row * kQK + cc * 16);
-          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc)) = widen8(raw[0], raw[1]);
-          *LDS_PTR(u32x4, lbase + lds_chunk(row, 2 * cc + 1)) = widen8(raw[2], raw[3]);
-        }
-        // (a position outside the retained set gets scale 1: its logit is set to -inf before the
-        // scale is applied and its weight is 0, so any finite positive value does)
-        if (tid < kTile) {
-          const bool ok = full || retained(pos0 + tid, L, p.S, p.Wu);
-          *LDS_PTR(float, lds_scales + (it & 3) * kScaleBytes + tid * 4) = ok ? sbase[tid] : 1.f;
+        for (int ci = lane; ci < kRowsPerWave * kChunksPerRow; ci += 64) {
+          const int r = ci / kChunksPerRow;
+          const int c = ci - r * kChunksPerRow;
+          const int row = row_w0 + r;
+          u32x4 v = {0, 0, 0, 0};
+          if (retained(pos0 + row, L, p.S, p.Wu)) v = *(const u32x4*)(gbase + row * kRowBytes + (c << 4));
+          *LDS_PTR(u32x4, lbase + lds_chunk(row, c)) = v;
         }
       }
       return ts;
@@ -360,18 +301,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       uint32_t l16 = lane << 4;
       asm volatile("" : "+v"(l16));
       const int row_w0 = wave * kRowsPerWave;
-      if constexpr (FP8) {
-        if constexpr (k < 5) {  // piece wave + 4 k of the tile's 18 pieces of 1 KB
-          const int c = wave + 4 * k;
-          const bool real = ts.mstride != 0 && c < kRawTileBytes / 1024;
-          dma_set_lds_base(real ? ts.lmain + c * 1024 : lds_junk);
-          dma16<0>(real ? ts.gbase : p.kv, (real ? c * 1024 : 0) + l16);
-        } else {  // the 32 scales (128 bytes): lanes 32..63 fetch the same words again
-          const bool real = ts.mstride != 0 && wave == 0;
-          dma_set_lds_base(real ? ts.lscale : lds_junk);
-          dma4(real ? (const uint8_t*)ts.sgbase : p.kv, (l16 >> 2) & 127);
-        }
-      } else if constexpr (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
+      if constexpr (k < kRowsPerWave) {  // main part: one instruction per row; lane l fetches chunk l ^ swz_main(row)
         constexpr int imm = (k & 3) * kMainRowBytes;
         const int row = row_w0 + k;
         if constexpr ((k & 3) == 0) dma_set_lds_base(ts.lmain + row * ts.mstride);
@@ -441,7 +371,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
       if (t < n_tiles) {
         const int pos0 = tile_pos(t);
         const uint64_t a = (uint64_t)(uintptr_t)p.kv +
-                           ((uint64_t)page_of[u] * kPage + (pos0 & (kPage - 1))) * (FP8 ? kQK : kRowBytes);
+                           ((uint64_t)page_of[u] * kPage + (pos0 & (kPage - 1))) * kRowBytes;
         *LDS_PTR(u32x2, lds_tiles + t * 8) = u32x2{(uint32_t)a | (uint32_t)tile_full(pos0), (uint32_t)(a >> 32)};
       }
     }
@@ -537,25 +467,6 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
     // fused multiply-add).  A masked-out position gets the raw value that maps to t = -inf.
     const float c = p.scale_log2;
     const float masked_raw = c < 0.f ? INFINITY : -INFINITY;
-    // fp8: the fp32 scale of the token behind element i, and all sixteen applied to S^T
-    // Elements 4 q .. 4 q + 3 of a lane are four consecutive tokens (8 q + 4 g ..): their
-    // scales are one 16-byte LDS read at a lane base plus a constant.  The base goes through
-    // an opaque move, or the compiler keeps one address register per element alive.
-    auto scale_base = [&](int slot) -> uint32_t {
-      uint32_t b = lds_scales + slot * kScaleBytes + g * 16;
-      asm volatile("" : "+v"(b));
-      return b;
-    };
-    auto tok_scale4 = [&](uint32_t base, int q) -> f32x4 { return *LDS_PTR(f32x4, base + q * 32); };
-    auto scale_logits = [&](f32x16& s, int slot) {
-      const uint32_t base = scale_base(slot);
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 sc = tok_scale4(base, q4);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) s[q4 * 4 + k] *= sc[k];
-      }
-    };
     auto mask_partial = [&](f32x16& s, int pos0) {
       const uint32_t vbits = valid_bits(pos0);
 #pragma unroll
@@ -604,7 +515,6 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           }
           settle_s(s);
           const int pos0 = tile_pos(0);
-          if constexpr (FP8) scale_logits(s, 0);
           if (!tile_full(pos0)) mask_partial(s, pos0);
           float mx = -INFINITY;
 #pragma unroll
@@ -620,19 +530,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             ref = m2 == -INFINITY ? 0.f : ceilf(m2);
           }
           float lsum = 0.f;
-          [[maybe_unused]] uint32_t sc_base = 0;
-          [[maybe_unused]] f32x4 sc4 = {0.f, 0.f, 0.f, 0.f};
-          if constexpr (FP8) sc_base = scale_base(0);
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const float t = fmaf(s[i], c, -ref);
             mt_all = fmaxf(mt_all, t);
-            float e = __builtin_amdgcn_exp2f(t);
+            const float e = __builtin_amdgcn_exp2f(t);
             lsum += e;
-            if constexpr (FP8) {
-              if ((i & 3) == 0) sc4 = tok_scale4(sc_base, i >> 2);
-              e *= sc4[i & 3];
-            }
             pn[i >> 3][i & 7] = (__bf16)e;
           }
           l_run = lsum;
@@ -658,10 +561,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
         uint32_t e_lo, e_hi;
         launder_offsets();
         if (n_tiles > 1) {
-          // bf16: tile 1 has arrived.  fp8: tile 1 was stored by this work group itself; the
-          // raw bytes of tile 2, which iteration 1 widens, must have arrived.
-          if constexpr (FP8) wait_vm<0>();
-          else wait_tile();
+          wait_tile();
           __syncthreads();  // tile 1 is visible
           ka = k_addr(lds0 + kStageBytes);
 #pragma unroll
@@ -678,55 +578,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
           const TileSrc ts = prep_tile_e(it + 2, e_lo, e_hi);
           uint32_t full_word = 1;
           float lsum = 0.f, mt = -INFINITY;
-          // fp8: the scales of the lane's 16 tokens, four at a time, each group requested while the
-          // group before it is in use; a scale multiplies the raw logit and, again, the weight
-          [[maybe_unused]] uint32_t sc_base = 0;
-          [[maybe_unused]] f32x4 sc4[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
           bf16x8 pf[2];  // weights of tile it-1, taken over from pn behind MFMA 2
-          // fp8: the raw bytes of tile it+1 (arrived and published by the previous iteration's
-          // barrier) are widened to bf16 into that tile's stage while S^T of tile `it` runs.
-          // Thread t handles row t / 8 and the nine 8-code pieces (t % 8) + 8 k of it (the row has
-          // 72): piece k is requested behind MFMA 6 + 3 k and stored, as one bf16 chunk, behind
-          // MFMA 8 + 3 k.  Every thread does the same nine steps for every tile index, without a
-          // branch: past the segment's end the pass turns stale bytes into a stage nobody reads,
-          // and a row outside the retained set (partial tiles; its contents are unspecified) is
-          // read from a row of zero codes instead.
-          [[maybe_unused]] uint32_t cv_src = 0, cv_d = 0, cv_dt = 0;
-          [[maybe_unused]] u32x2 cv_raw = {0, 0};
-          auto convert_step = [&](auto m_tag) {
-            constexpr int m = decltype(m_tag)::value;
-            if constexpr (m == 3) {
-              uint32_t t = tid;
-              asm volatile("" : "+v"(t));
-              const uint32_t row = t >> 3, t8 = t & 7;
-              const uint32_t e_next = __builtin_amdgcn_readfirstlane(
-                  *LDS_PTR(uint32_t, lds_tiles + (it + 1 < kMaxSegTiles ? it + 1 : kMaxSegTiles - 1) * 8));
-              const bool next_full = e_next & 1;  // wave-uniform
-              const int pos_next = tile_pos(it + 1);
-              const bool rowok = next_full || retained(pos_next + (int)row, L, p.S, p.Wu);
-              cv_src = (rowok ? lds_rawbuf + ((it + 1) & 1) * kRawTileBytes + row * kQK : lds_zero) + t8 * 8;
-              const uint32_t sw = swz_main(row);
-              cv_d = st_next + row * kMainRowBytes + (((t8 ^ (sw & 7)) | (sw & 8)) << 4);
-              cv_dt = st_next + kTailBase + row * kTailRowBytes + ((t8 ^ swz_tail(row)) << 4);
-              // scales of positions outside the retained set: see the synchronous fill of tiles 0, 1
-              if (!next_full && it + 1 < n_tiles) {
-                if (t < (uint32_t)kTile && !retained(pos_next + (int)t, L, p.S, p.Wu))
-                  *LDS_PTR(float, lds_scales + ((it + 1) & 3) * kScaleBytes + t * 4) = 1.f;
-              }
-            }
-            if constexpr (m >= 6 && m <= 30 && (m - 6) % 3 == 0) {
-              constexpr int k = (m - 6) / 3;
-              cv_raw = *LDS_PTR(u32x2, cv_src + 64 * k);
-            }
-            if constexpr (m >= 8 && m <= 32 && (m - 8) % 3 == 0) {
-              constexpr int k = (m - 8) / 3;
-              const u32x4 w = widen8(cv_raw.x, cv_raw.y);
-              // piece k is bf16 chunk t8 + 8 k of the row: chunk position (t8 + 8 k) ^ swizzle
-              if constexpr (k == 8) *LDS_PTR(u32x4, cv_dt) = w;
-              else if constexpr (k & 1) *LDS_PTR(u32x4, (cv_d ^ 128u) + (k >> 1) * 256) = w;
-              else *LDS_PTR(u32x4, cv_d + (k >> 1) * 256) = w;
-            }
-          };
           // One MFMA and what is issued behind it; m is a compile-time constant.
           auto step = [&](auto m_tag) {
             constexpr int m = decltype(m_tag)::value;
@@ -750,14 +602,10 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               e_lo = __builtin_amdgcn_readfirstlane(e_tab.x);
               e_hi = __builtin_amdgcn_readfirstlane(e_tab.y);
             }
-            // the direct loads of tile it+2.  bf16: one every four MFMAs of the S^T phase (whose
-            // MFMAs leave issue slots free; the PV phase, with two LDS reads and a softmax element
-            // per MFMA, has none to spare).
-            // fp8: behind the first six MFMAs, so that the raw bytes have the whole iteration
-            // to arrive before the barrier behind MFMA 63 hands them to the next iteration.
-            if constexpr (!FP8 && m % 4 == 1 && m / 4 < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m / 4>{});
-            if constexpr (FP8 && m < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m>{});
-            if constexpr (FP8) convert_step(m_tag);
+            // the direct loads of tile it+2: one every four MFMAs of the S^T phase (whose MFMAs
+            // leave issue slots free; the PV phase, with two LDS reads and a softmax element per
+            // MFMA, has none to spare)
+            if constexpr (m % 4 == 1 && m / 4 < kDmaPerTile) dma_piece(ts, std::integral_constant<int, m / 4>{});
             // LDS addresses, formed in registers whose previous contents are no longer needed:
             // V of tile it-1 behind MFMAs 20 .. 27 (K addresses 0 .. 3 are done with), the
             // next iteration's K behind MFMAs 60 .. 62
@@ -781,17 +629,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
               // Tile it+1 becomes visible, and every wave is done with tile it-1 (its last
               // fragments were requested behind MFMA 59 and the barrier's fence waits for
               // them), whose stage the direct loads of the next iteration overwrite.
-              if constexpr (FP8) wait_vm<0>();  // the raw bytes of tile it+2 (and tile it+1 is widened)
-              else wait_tile();
+              wait_tile();
               __syncthreads();
 #pragma unroll
               for (int d = 4; d < 8; ++d) fr[d] = load_k(ka, d);
             }
             constexpr int j = m - kNK;
-            if constexpr (FP8 && m == 33) {
-              sc_base = scale_base(it & 3);
-              sc4[0] = tok_scale4(sc_base, 0);
-            }
             if constexpr (j == 0) {
               if (!(full_word & 1)) {  // wave-uniform and rare
                 settle_s(s);
@@ -805,16 +648,10 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_kernel(DecodeParams p) {
             if constexpr (j >= kFirst) {
               constexpr int i = ((j - kFirst) * 16) / (kNV - kFirst), i1 = ((j + 1 - kFirst) * 16) / (kNV - kFirst);
               if constexpr (i1 > i) {  // at most one element per MFMA
-                float raw = s[i];
-                if constexpr (FP8) {
-                  if constexpr ((i & 3) == 0 && i < 12) sc4[((i >> 2) + 1) & 1] = tok_scale4(sc_base, (i >> 2) + 1);
-                  raw *= sc4[(i >> 2) & 1][i & 3];
-                }
-                const float t = fmaf(raw, c, -ref);
+                const float t = fmaf(s[i], c, -ref);
                 mt = fmaxf(mt, t);
-                float e = __builtin_amdgcn_exp2f(t);
+                const float e = __builtin_amdgcn_exp2f(t);
                 lsum += e;
-                if constexpr (FP8) e *= sc4[(i >> 2) & 1][i & 3];
                 pn[i >> 3][i & 7] = (__bf16)e;
               }
             }
@@ -940,15 +777,15 @@ __global__ void xcd_probe_kernel(int* out) {
   if (threadIdx.x == 0) out[blockIdx.x] = (int)xcc_id();
 }
 
-template <int WAVES, bool FP8>
+template <int WAVES>
 static hipError_t set_lds_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<WAVES, FP8>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<WAVES>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
 }
 
 hipError_t init_kernels() {
   hipError_t e;
-  if ((e = set_lds_attr<4, false>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<4>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -958,7 +795,7 @@ hipError_t launch_decode(const DecodeParams& p, int waves, int n_units, hipStrea
   if (p.xcds < 1) return hipErrorInvalidValue;
   // the grid is rounded up to a multiple of the XCD count (see the unit mapping in the kernel)
   dim3 grid(((n_units + p.xcds - 1) / p.xcds) * p.xcds), block(waves * 64);
-  hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, kLdsBytes, stream, p);
+  hipLaunchKernelGGL((decode_kernel<4>), grid, block, kLdsBytes, stream, p);
   return hipGetLastError();
 }
 

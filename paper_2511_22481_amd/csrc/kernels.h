@@ -47,7 +47,7 @@ struct CombineParams {
   const float* part_lse;
   void* out;
   float* lse;
-  int H, head_block, out_fp32;
+  int H, head_block, out_fp32, n_items;
 };
 
 struct AppendParams {
