@@ -33,23 +33,29 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 WORKLOAD = "r1_b64_32k"
 # HBM bytes per launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this file (profiles/decode_kernel_r1_b64_32k_hbm_counters.md), scaled by what the same
+# this file (profiles/*_hbm_counters.md), scaled by what the same
 # counters read for a 1 GiB device copy.  The figure belongs to one version of the kernel
 # source: it is reported only while the source's hash is the one the counters were taken
 # with, and as null from the next kernel change on until they are taken again.
 MEASURED_TRAFFIC = {
-    "r1_b64_32k": {"bytes": 170_635_500 + 36_044_800,
-                   "kernel_sha256": "0" * 64},
+    "r1_b64_32k": {"bytes": 170_634_110 + 36_044_800,
+                   "sources": ("decode_kernels.hip", "decode_common.h"),
+                   "kernel_sha256": "5bf9386f7d7f68bd707b1121e07a2e05465b0f6523fd327623270702fd637932"},
+    "fp8_b32_128k": {"bytes": 167_626_321 + 38_349_034,
+                     "sources": ("decode_fp8_kernel.hip", "decode_common.h"),
+                     "kernel_sha256": "0e7661a2774e53bcd42f0241148f4aeddd047ff11933c607d7a5c7b9cd79ddd9"},
 }
-KERNEL_SOURCE = os.path.join(ROOT, "paper_2511_22481_amd", "csrc", "decode_kernels.hip")
+CSRC = os.path.join(ROOT, "paper_2511_22481_amd", "csrc")
 
 
 def measured_traffic(workload):
     rec = MEASURED_TRAFFIC.get(workload)
     if not rec:
         return None
-    sha = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
-    return rec["bytes"] if sha == rec["kernel_sha256"] else None
+    h = hashlib.sha256()
+    for name in rec["sources"]:
+        h.update(open(os.path.join(CSRC, name), "rb").read())
+    return rec["bytes"] if h.hexdigest() == rec["kernel_sha256"] else None
 
 
 def algorithmic_bytes(retained_tokens, batch, heads, kv_dtype):
@@ -217,7 +223,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if not fp8 else "fp8_e4m3 cache, bf16 mfma",
+        "dtype": "bf16" if not fp8 else "fp8_e4m3",
         "data": "synthetic",
         "config": {
             "workload": f"{cfg.name}: B={cfg.batch} H={cfg.heads} L={cfg.ctx} S={cfg.sink} "
