@@ -244,7 +244,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "decode_kernel (main pass; combine excluded)",
+            "kernel": ("decode_fp8_kernel" if fp8 else "decode_kernel") + " (main pass; combine excluded)",
             "achieved": achieved,
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
