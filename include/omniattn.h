@@ -154,7 +154,8 @@ int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t til
  *   q          device, bf16 [B, H, 576] contiguous (absorbed queries); [B, T, H, 576]
  *              for q_len = T > 1, and out / lse likewise [B, T, H, 512] / [B, T, H]
  *   kv_cache   device, bf16 or e4m3 bytes [num_pages, 128, 576] contiguous
- *   kv_scales  device, fp32 [num_pages, 128]; NULL unless kv_dtype is fp8
+ *   kv_scales  device, fp32 [num_pages, 128]; NULL unless kv_dtype is fp8.  Scales of
+ *              retained tokens are finite and >= 0 (zero: a row of zeros).
  *   page_table device, int32 [B, max_pages_per_seq]; entry i of row b is the
  *              physical page of logical tokens [128 i, 128 i + 128).  Entries of
  *              pages that hold no retained token are never read.
@@ -170,6 +171,14 @@ int omniattn_plan_tile_range(const omniattn_plan_t* plan, int32_t b, int32_t til
  * (NaN included) without effect.  Page ids of retained pages must lie in
  * [0, num_pages): the kernel does not check device-side contents.
  * Same plan + same inputs give bitwise identical results (nothing is accumulated atomically).
+ * Arithmetic: bf16 cache - bf16 matrix products with fp32 accumulation, softmax weights
+ * rounded to bf16.  fp8 cache - both products on the 8-bit matrix instruction; the query
+ * enters as two e4m3 terms (exact for all but elements below 2^-14 of the row's largest), so
+ * logits and lse carry fp32 accumulation error only; the softmax weights, with the token's
+ * scale folded in, are rounded to e4m3 (relative 2^-4 per weight) and out is normalised by
+ * the sum of the rounded weights.  A token whose scale is more than 2^10 below the largest
+ * scale of its 64-token tile has its value row taken at 2^-10 of that largest scale (its
+ * softmax weight counts in full).
  */
 int omniattn_decode(const omniattn_plan_t* plan, const void* q, const void* kv_cache,
                     const float* kv_scales, const int32_t* page_table, void* out,

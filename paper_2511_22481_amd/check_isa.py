@@ -87,12 +87,12 @@ def check(asm_text, kernel_filter="decode_kernel"):
             writes_first = (op.startswith("v_") and not op.startswith("v_cmp")) or "_load" in op or \
                 op.startswith("ds_read") or op.startswith("ds_bpermute")
             read_text = ",".join(operands[1:]) if writes_first else rest
-            for r in _regs(read_text):
+            for r in sorted(_regs(read_text)):
                 if r in pending and pending[r] < need + extra.get(r, 0):
                     problems.append(f"line {lineno}: {pending[r]} wait states after MFMA write of "
                                     f"{r[0]}{r[1]}: {line}")
             if writes_first:  # overwritten: later uses no longer see the MFMA's result
-                for r in _regs(operands[0]):
+                for r in sorted(_regs(operands[0])):
                     if r in pending:
                         if pending[r] < VALU_STATES + extra.get(r, 0):
                             problems.append(f"line {lineno}: overwrite {pending[r]} wait states after MFMA "

@@ -48,8 +48,8 @@ constexpr int kScale8 = kT8 * 4;                // fp32 scales of one tile
 constexpr int kTileTab8 = kMaxSegTiles * 8;
 constexpr int kJunk8 = 4096;
 constexpr int kWaves8 = 4;
-// stages | scale slots | per-wave reciprocal scales | retry flag | tile table | junk
-constexpr int kLds8 = kStages8 * (kStage8 + kScale8) + kWaves8 * kScale8 + 16 + kTileTab8 + kJunk8;
+// stages | scale slots | per-wave weight scales and their reciprocals | retry flag | tile table | junk
+constexpr int kLds8 = kStages8 * (kStage8 + kScale8) + kWaves8 * 2 * kScale8 + 16 + kTileTab8 + kJunk8;
 static_assert(kLds8 <= 160 * 1024, "LDS of one compute unit");
 
 // LDS layout of a stage: the first 512 bytes of the 64 rows (row r at 512 r), then their 64
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kWaves8 * 64, 1) void decode_fp8_kernel(DecodeParam
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds_raw;
   const uint32_t lds_scales = lds0 + kStages8 * kStage8;
   const uint32_t lds_rscale = lds_scales + kStages8 * kScale8;
-  const uint32_t lds_flag = lds_rscale + WAVES * kScale8;
+  const uint32_t lds_flag = lds_rscale + WAVES * 2 * kScale8;
   const uint32_t lds_tiles = lds_flag + 16;
   const uint32_t lds_junk = lds_tiles + kTileTab8;
   const int tid = threadIdx.x;
@@ -430,14 +430,20 @@ __global__ __launch_bounds__(kWaves8 * 64, 1) void decode_fp8_kernel(DecodeParam
     };
     auto tok4 = [&](uint32_t base, int h, int q) -> f32x4 { return *LDS_PTR(f32x4, base + h * 128 + q * 32); };
     auto tok2 = [&](uint32_t base, int h, int q, int w) -> f32x2 { return *LDS_PTR(f32x2, base + h * 128 + q * 32 + w * 8); };
-    // Reciprocal scales of the tile in `stage`, for this wave's own use (lane = token); returns
-    // es with every scale of the tile < 2^es (wave-uniform).  The maximum runs down each row of
-    // 16 lanes by shifted moves; the four row ends are read out and combined on the scalar side.
+    // Weight scales of the tile in `stage` and their reciprocals, for this wave's own use (lane =
+    // token); returns es with every scale of the tile < 2^es (wave-uniform, at least -100).  The
+    // weight of token j goes to the matrix instruction as round(w_j * scale_j), so a token whose
+    // scale lies far below the tile's largest would underflow e4m3 and drop out of the rounded
+    // weights' sum although its softmax weight counts.  Its weight scale is therefore raised to
+    // 2^(es - 10): the sum stays right (also for a scale of zero), and its value row, at most
+    // 2^-10 of the tile's largest values, enters the output that much too large at worst.  The
+    // logits keep the true scale.
+    // The maximum runs down each row of 16 lanes by shifted moves; the four row ends are read out
+    // and combined on the scalar side.
     auto prep_rscale = [&](uint32_t stage) -> int {
       uint32_t l = lane;
       asm volatile("" : "+v"(l));
       const float sc = *LDS_PTR(float, lds_scales + stage * kScale8 + l * 4);
-      *LDS_PTR(float, lds_rscale + wave * kScale8 + l * 4) = __builtin_amdgcn_rcpf(sc);
       uint32_t m = __builtin_bit_cast(uint32_t, sc) & 0x7fffffffu;  // positive floats order like integers
 #define OA_ROW_SHR_MAX(n)                                                                        \
   {                                                                                              \
@@ -449,7 +455,13 @@ __global__ __launch_bounds__(kWaves8 * 64, 1) void decode_fp8_kernel(DecodeParam
       const uint32_t a = __builtin_amdgcn_readlane(m, 15), b = __builtin_amdgcn_readlane(m, 31);
       const uint32_t c = __builtin_amdgcn_readlane(m, 47), d = __builtin_amdgcn_readlane(m, 63);
       const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
-      return (int)((ab > cd ? ab : cd) >> 23) - 126;
+      int es = (int)((ab > cd ? ab : cd) >> 23) - 126;
+      es = es < -100 ? -100 : es;
+      // (a NaN scale reaches the output through the logits; here the maximum drops it)
+      const float wsc = fmaxf(sc, __builtin_amdgcn_ldexpf(1.0f, es - 10));
+      *LDS_PTR(float, lds_rscale + wave * 2 * kScale8 + l * 4) = wsc;
+      *LDS_PTR(float, lds_rscale + wave * 2 * kScale8 + kScale8 + l * 4) = __builtin_amdgcn_rcpf(wsc);
+      return es;
     };
     // Pass A over quads [q_lo, q_hi) of one half: raw logit -> u = s * scale_token, in place, or
     // -inf where the lane's validity bit is clear (two bit operations per element, without a
@@ -514,7 +526,8 @@ __global__ __launch_bounds__(kWaves8 * 64, 1) void decode_fp8_kernel(DecodeParam
 
         // Pass B over elements 4 q + 2 w, 4 q + 2 w + 1 of one half: u -> weight
         // 2^(u c - ref - kk) * scale, rounded to e4m3 into the lane's B operand (bytes 16 h + 4 q
-        // + 2 w, + 1); exact and rounded sums.  sc, rs: the quad's scales and their reciprocals.
+        // + 2 w, + 1); exact and rounded sums.  sc, rs: the quad's weight scales (prep_rscale) and
+        // their reciprocals.
         auto pass_b2 = [&](f32x16& s, auto h_tag, auto q_tag, auto w_tag, uint32_t sbase, uint32_t rbase, float rk,
                            float& lsum, float& lqsum) {
           constexpr int h = decltype(h_tag)::value, q = decltype(q_tag)::value, w = decltype(w_tag)::value;
@@ -566,7 +579,8 @@ __global__ __launch_bounds__(kWaves8 * 64, 1) void decode_fp8_kernel(DecodeParam
           float mu0 = -INFINITY, mu1 = -INFINITY, ls = 0.f, lq = 0.f, rk0 = 0.f, rk1 = 0.f;
           int es = 0, kk0 = 0, kk1 = 0, pn_s = 127;
           auto sb = [&]() { return scale_base(lds_scales + stage_of(it) * kScale8); };
-          auto rb = [&]() { return scale_base(lds_rscale + wave * kScale8); };
+          auto wb = [&]() { return scale_base(lds_rscale + wave * 2 * kScale8); };
+          auto rb = [&]() { return scale_base(lds_rscale + wave * 2 * kScale8 + kScale8); };
           // the half's block exponent (the same in both lanes of a head) and what pass B subtracts
           auto close_half = [&](float& mu, int& kk, float& rk) {
             const float mt = pair_max(fmaf(mu, c_head, -ref));  // -inf stays -inf (c_head > 0)
@@ -618,7 +632,7 @@ __global__ __launch_bounds__(kWaves8 * 64, 1) void decode_fp8_kernel(DecodeParam
             if constexpr (m >= 23 && m < 31) {
               constexpr int q = (m - 23) / 2, w = (m - 23) & 1;
               pass_b2(s0, std::integral_constant<int, 0>{}, std::integral_constant<int, q>{}, std::integral_constant<int, w>{},
-                      sb(), rb(), rk0, ls, lq);
+                      wb(), rb(), rk0, ls, lq);
             }
             if constexpr (m == 31) {
               l_run += __builtin_amdgcn_ldexpf(ls, kk0);
@@ -643,7 +657,7 @@ __global__ __launch_bounds__(kWaves8 * 64, 1) void decode_fp8_kernel(DecodeParam
                 (([&] {
                    constexpr int q = E / 2, w = E & 1;
                    pass_b2(s1, std::integral_constant<int, 1>{}, std::integral_constant<int, q>{},
-                           std::integral_constant<int, w>{}, sb(), rb(), rk1, ls, lq);
+                           std::integral_constant<int, w>{}, wb(), rb(), rk1, ls, lq);
                  }()),
                  ...);
               }(std::make_integer_sequence<int, 8>{});

@@ -223,6 +223,27 @@ def test_fp8_cache(q_std):
     parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what="fp8")
 
 
+@pytest.mark.parametrize("spread", [0, 12, 24])
+def test_fp8_token_scales_of_very_different_size(spread):
+    """Token scales spread over 2^-spread .. 1 inside every tile, and a few scales of exactly zero
+    (an all-zero row: value 0, logit 0, yet a full softmax weight: tokens of small scale have
+    logits near zero, so their weights are as large as anyone's).  The kernel folds the scale into
+    the e4m3 weight; a token far below its tile's largest scale must still count in the
+    normaliser, and a zero scale must not produce NaN.  (The values scale with the token scale, so
+    the output is dominated by the large-scale tokens and the absolute bound follows its size.)"""
+    lens = [1500, 257, 2176, 65, 700]
+    inp = make_custom(5, 64, lens, 64, 512, seed=31 + spread, kv_dtype="fp8", q_std=0.3, kv_std=1.0)
+    g = torch.Generator().manual_seed(7 + spread)
+    e = torch.randint(-spread, 1, inp.kv_scales.shape, generator=g)
+    inp.kv_scales = inp.kv_scales * torch.exp2(e.float())
+    zero = torch.rand(inp.kv_scales.shape, generator=g) < 0.02
+    inp.kv_scales[zero] = 0.0
+    inp = parity.to_device(inp)
+    out, lse, _ = parity.run_gpu(inp, out_dtype=torch.float32)
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+    parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what=f"fp8 scales 2^-{spread}..1")
+
+
 def test_many_short_sequences_share_work_units():
     """bf16 cache, more sequences than compute units: several segments per work unit, with
     one-tile and two-tile segments among them (the MFMA stream's shortest paths)."""
@@ -236,7 +257,7 @@ def test_many_short_sequences_share_work_units():
 
 def test_fp8_many_short_sequences_share_work_units():
     """More sequences than compute units: every work unit runs several segments, so the
-    tile pipeline (direct loads, widening pass, scale slots) restarts inside one launch."""
+    tile pipeline (direct loads, query split, scale slots) restarts inside one launch."""
     rng = np.random.default_rng(17)
     lens = [int(x) for x in rng.integers(33, 420, size=600)]
     inp = parity.to_device(make_custom(600, 16, lens, 32, 200, seed=21, kv_dtype="fp8", q_std=0.3, kv_std=1.0))
