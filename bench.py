@@ -33,7 +33,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 WORKLOAD = "r1_b64_32k"
 # HBM bytes per launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this file (profiles/*_hbm_counters.md), scaled by what the same
+# this file (their summaries are kept under profiles/), scaled by what the same
 # counters read for a 1 GiB device copy.  The figure belongs to one version of the kernel
 # source: it is reported only while the source's hash is the one the counters were taken
 # with, and as null from the next kernel change on until they are taken again.
