@@ -89,6 +89,50 @@ def test_fp32_output():
         assert float((out.to(torch.bfloat16).float() - out16.float()).abs().max()) <= 0.02 * float(out.abs().max())
 
 
+# -------------------------------------------------------------------- arithmetic edge cases ---
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_negative_softmax_scale(kv_dtype):
+    """The scale is any fp32: a negative one turns the softmax towards the smallest q.k (the fp8
+    kernel moves the sign into its query terms)."""
+    inp = make_custom(3, 48, [700, 130, 2100], 32, 300, seed=41, kv_dtype=kv_dtype, q_std=0.5, kv_std=1.0,
+                      softmax_scale=-(192.0 ** -0.5))
+    inp = parity.to_device(inp)
+    out, lse, _ = parity.run_gpu(inp, out_dtype=torch.float32)
+    parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what=f"negative scale {kv_dtype}")
+
+
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_query_rows_of_zeros_and_of_wide_dynamic_range(kv_dtype):
+    """Head 0: q = 0 (uniform softmax: the mean of the kept values, lse = ln |M|).  Head 1: elements
+    from 2^-20 to 1 of the row maximum in one row (the fp8 kernel's two-term query is exact down to
+    2^-14 of the maximum and keeps 2^-22 of it below that).  Head 2: a row scaled by 2^40, the
+    softmax scale undoing it."""
+    lens = [900, 64, 1300]
+    inp = make_custom(3, 32, lens, 16, 500, seed=43, kv_dtype=kv_dtype, q_std=1.0, kv_std=1.0)
+    g = torch.Generator().manual_seed(5)
+    inp.q[:, 0] = 0
+    e = torch.randint(-20, 1, (3, 576), generator=g).float()
+    inp.q[:, 1] = (inp.q[:, 1].float() * torch.exp2(e)).to(torch.bfloat16)
+    inp = parity.to_device(inp)
+    out, lse, _ = parity.run_gpu(inp, out_dtype=torch.float32)
+    e_ = parity.assert_parity(inp, out, lse, row_rel_l2=2e-2, what=f"q rows {kv_dtype}")
+    kept = torch.tensor([min(L, 16) + min(L - min(L, 16), 500) if L > 16 else L for L in lens], dtype=torch.float64)
+    assert torch.allclose(lse[:, 0].double().cpu(), kept.log(), atol=1e-5), (lse[:, 0], kept.log())
+    # the whole problem scaled: q * 2^40, softmax scale / 2^40
+    import dataclasses
+    big = dataclasses.replace(inp, q=(inp.q.float() * 2.0 ** 40).to(torch.bfloat16), softmax_scale=inp.softmax_scale * 2.0 ** -40)
+    out2, lse2, _ = parity.run_gpu(big, out_dtype=torch.float32)
+    assert torch.allclose(out2, out, atol=1e-6, rtol=1e-5) and torch.allclose(lse2, lse, atol=1e-5)
+
+
+def test_fp8_retained_nan_code_propagates():
+    inp = parity.to_device(make_custom(2, 32, [300, 300], 10, 20, seed=2, kv_dtype="fp8", q_std=1.0, kv_std=1.0))
+    page = int(inp.page_table[0, 0])
+    inp.kv_cache[page, 3, 100] = float("nan")            # e4m3 NaN code; position 3 is a sink of sequence 0
+    out, lse, _ = parity.run_gpu(inp)
+    assert torch.isnan(out[0].float()).all() and not torch.isnan(out[1].float()).any()
+
+
 # ---------------------------------------------------------------------------- invariants ---
 def test_poisoned_unretained_slots_have_no_influence():
     lens = [1000, 77, 400, 2600]
